@@ -1,0 +1,251 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-reclaim hot path on one MI355X.
+
+A step is one pass of the whole path over one seeded synthetic workload:
+kv_plan_reclaim -> kv_compact -> kv_remap_tables, back to back on one HIP
+stream with no host synchronisation in between (the block tables are restored
+from a pristine device copy at the start of each step, a 2 MiB device copy, so
+that every step does identical work; replaying the block copy needs no
+restore because source blocks are never written).
+
+Prints ONE JSON line.  `value` is read+write GB/s of the whole step with
+inputs resident in HBM; `roofline` prices the block-copy kernel alone against
+the 8 TB/s HBM peak using HIP-event times taken on the launch stream;
+`cpu_baseline` is the single-threaded CPU oracle timed on a bounded sample of
+the same workload; `materialize` adds the weight-streaming leg of the third
+configuration (pinned host -> reclaimed region) serial and overlapped.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+LINK_PEAK_GBPS = 63.0           # PCIe 5.0 x16, one direction, theoretical
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into the benchmark config list (default 1: 8B-shaped)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-materialize", action="store_true")
+    ap.add_argument("--workgroups", type=int, default=0)
+    ap.add_argument("--chunk-bytes", type=int, default=0)
+    ap.add_argument("--flags", type=int, default=0)
+    return ap.parse_args()
+
+
+def cpu_baseline(cfg, w, sample_moves: int):
+    """The oracle as it stands, one thread, on the first `sample_moves` moves of this workload."""
+    import oracle
+    t0 = time.perf_counter()
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    t_plan = time.perf_counter() - t0
+    m = min(sample_moves, p.n_moves)
+    bb = cfg.block_bytes
+    pool = np.empty(cfg.pool_bytes, dtype=np.uint8)       # virtual; only sampled blocks get touched
+    blocks = pool.reshape(cfg.num_blocks, bb)
+    pattern = np.random.default_rng(cfg.seed).integers(0, 256, bb, dtype=np.uint8)
+    for k in range(m):
+        blocks[p.src[k]] = pattern                         # sources hold bytes, destinations are faulted in
+        blocks[p.dst[k]] = 0
+    sample = oracle.Plan(0, p.src[:m], p.dst[:m], p.new_id, p.live_out, m, cfg.num_blocks, cfg.boundary)
+    t0 = time.perf_counter()
+    oracle.compact(pool, bb, sample)
+    t_compact = time.perf_counter() - t0
+    tables = w.tables.copy()
+    t0 = time.perf_counter()
+    oracle.remap(tables, p)
+    t_remap = time.perf_counter() - t0
+    total = t_plan + t_compact + t_remap
+    del pool
+    return {"value": round(2 * m * bb / total / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "host_cores_available": os.cpu_count(),
+            "sample": f"oracle plan (all {cfg.num_blocks} blocks) + block copy of the first {m} of {p.n_moves} moves "
+                      f"({m * bb / 2**30:.2f} GiB moved) + table remap (all {tables.size} entries), one thread",
+            "ms": {"plan": round(t_plan * 1e3, 3), "compact_sample": round(t_compact * 1e3, 3),
+                   "remap": round(t_remap * 1e3, 3)}}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
+              "there is no multi-GPU path to measure. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2512_09472_amd as wk
+    from synth import CONFIGS, content, dense_offsets, make_workload, weight_shapes_8b
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    wk.binding.load()
+    dev = torch.device("cuda:0")
+    cfg = CONFIGS[args.config]
+    w = make_workload(cfg)
+    bb = cfg.block_bytes
+
+    # ---- device-resident inputs
+    pool_t = torch.empty(cfg.pool_bytes, dtype=torch.uint8, device=dev)
+    table = content.normal_bf16_table(1.0) if cfg.content == "bf16_normal" else None
+    table_d = torch.from_numpy(table.view(np.int16)).to(dev) if table is not None else None
+    content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed,
+                        table_ptr=table_d.data_ptr() if table_d is not None else 0)
+    live_d = torch.from_numpy(w.live.view(np.int64)).to(dev)
+    tables0_d = torch.from_numpy(w.tables).to(dev)
+    tables_d = tables0_d.clone()
+    ws_bytes = wk.kv_plan_workspace_bytes(cfg.num_blocks, cfg.boundary)
+    ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
+    plan = wk.kv_plan_bind(ws, ws_bytes, cfg.num_blocks, cfg.boundary)
+    pool = wk.pool_desc(pool_t, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    stream = torch.cuda.Stream()
+    s = stream.cuda_stream
+    tuning = dict(workgroups=args.workgroups, chunk_bytes=args.chunk_bytes, flags=args.flags)
+
+    def step(ev=None):
+        with torch.cuda.stream(stream):
+            tables_d.copy_(tables0_d, non_blocking=True)
+        wk.kv_plan_reclaim(live_d, plan, s)
+        if ev is not None:
+            ev[0].record(stream)
+        wk.kv_compact_launch(pool, plan, s, **tuning)
+        if ev is not None:
+            ev[1].record(stream)
+        wk.kv_remap_tables(tables_d, w.tables.shape[0], w.tables.shape[1], plan, s)
+
+    torch.cuda.synchronize()
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    st = wk.kv_plan_fetch(plan, s)
+    if st.status != wk.KV_OK:
+        print(f"bench.py: plan status {st.status}", file=sys.stderr)
+        sys.exit(1)
+    n_moves = st.n_moves
+    rw_bytes = 2 * n_moves * bb
+
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    compact_ms = [a.elapsed_time(b) for a, b in events]
+    compact_avg = sum(compact_ms) / len(compact_ms)
+    st = wk.kv_plan_fetch(plan, s)
+    assert st.status == wk.KV_OK and st.n_moves == n_moves and st.n_bad_entries == 0
+
+    reclaimed_bytes = (cfg.num_blocks - cfg.boundary) * bb
+    out = {
+        "metric": "kv_compaction_GBps_read_plus_write",
+        "value": round(rw_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"configs[{cfg.index}] {cfg.name}: {cfg.num_layers} layers, block {bb} B, "
+                               f"{cfg.num_blocks} blocks ({cfg.pool_bytes / 2**30:.0f} GiB pool), boundary {cfg.boundary}, "
+                               f"{w.live_count} live, {n_moves} moved",
+                   "step": "kv_plan_reclaim + kv_compact + kv_remap_tables on one stream",
+                   "moved_GiB": round(n_moves * bb / 2**30, 3),
+                   "reclaimed_GiB": round(reclaimed_bytes / 2**30, 3),
+                   "ms_to_reclaim": round(ms_per_step, 4),
+                   "pct_of_hbm_peak_whole_step": round(100 * rw_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
+                   "tuning": tuning},
+        "roofline": {"bound": "hbm", "kernel": "compact_kernel",
+                     "achieved": round(rw_bytes / (compact_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(rw_bytes / (compact_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                     "traffic": None,
+                     "kernel_ms_avg": round(compact_avg, 4), "kernel_ms_min": round(min(compact_ms), 4),
+                     "kernel_ms_median": round(statistics.median(compact_ms), 4),
+                     "algorithmic_bytes_per_launch": rw_bytes},
+    }
+
+    # ---- weight materialisation leg (third configuration: same pool plus weights)
+    if not args.no_materialize and cfg.index in (1, 2):
+        shapes = weight_shapes_8b()
+        sizes = [2 * a * b for _, (a, b) in shapes]
+        offs = dense_offsets(sizes)
+        total = sum(sizes)
+        host = torch.empty(total, dtype=torch.uint8, pin_memory=True)
+        wtab = torch.from_numpy(content.normal_bf16_table(0.02).view(np.int16)).to(dev)
+        stage = torch.empty(max(sizes), dtype=torch.uint8, device=dev)
+        pos = 0
+        for i, sz in enumerate(sizes):       # seeded N(0, 0.02) bf16, generated on the device, parked in pinned memory
+            content.fill_device(stage.data_ptr(), 1, sz, 0x5EED0002, cid0=i, table_ptr=wtab.data_ptr())
+            host[pos:pos + sz].copy_(stage[:sz])
+            pos += sz
+        torch.cuda.synchronize()
+        del stage
+        tensors, pos = [], 0
+        for sz, off in zip(sizes, offs):
+            tensors.append((host.data_ptr() + pos, sz, off))
+            pos += sz
+        copy_stream = torch.cuda.Stream()
+        cs = copy_stream.cuda_stream
+
+        def timed(fn, reps=3):
+            ts = []
+            for _ in range(reps):
+                torch.cuda.synchronize()
+                a = time.perf_counter()
+                fn()
+                torch.cuda.synchronize()
+                ts.append((time.perf_counter() - a) * 1e3)
+            return min(ts)
+
+        def only_copy():
+            wk.weights_materialize(pool, cfg.boundary, tensors, cs, None)
+
+        def serial():
+            step()
+            torch.cuda.synchronize()
+            wk.weights_materialize(pool, cfg.boundary, tensors, cs, None)
+
+        done = torch.cuda.Event()
+
+        def overlapped():
+            with torch.cuda.stream(stream):
+                tables_d.copy_(tables0_d, non_blocking=True)
+            wk.kv_plan_reclaim(live_d, plan, s)
+            wk.kv_compact_launch(pool, plan, s, **tuning)
+            done.record(stream)
+            wk.weights_materialize(pool, cfg.boundary, tensors, cs, done.cuda_event)
+            wk.kv_remap_tables(tables_d, w.tables.shape[0], w.tables.shape[1], plan, s)
+
+        only_copy()
+        t_copy = timed(only_copy)
+        t_serial = timed(serial)
+        t_overlap = timed(overlapped)
+        out["materialize"] = {"workload": "configs[2]: 225 bf16 tensors, 15,009,316,864 B from pinned host memory",
+                              "h2d_ms": round(t_copy, 2), "h2d_GBps": round(total / t_copy / 1e6, 2),
+                              "link_peak_GBps": LINK_PEAK_GBPS,
+                              "frac_of_link_peak": round(total / t_copy / 1e6 / LINK_PEAK_GBPS, 4),
+                              "serial_reclaim_then_copy_ms": round(t_serial, 2),
+                              "overlapped_ms": round(t_overlap, 2)}
+        del host
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, w, sample_moves=2048)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

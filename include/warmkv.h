@@ -1,0 +1,182 @@
+/* warmkv - MI355X (gfx950) KV-cache reclaim and weight materialisation.
+ *
+ * The scenario is the paper's proactive prewarming (arXiv 2512.09472, Sec. 3.3
+ * and App. C, Fig. 4b steps 1-3): a serving instance that is about to be shut
+ * down keeps only the KV space it reserved (Eq. 4) and gives the rest to the
+ * weights of a model being prewarmed, while its running requests carry on.
+ * Only unused KV blocks may receive weights, and the engine must keep seeing
+ * every sequence's KV unchanged.  The paper gets there by re-pointing page
+ * tables; this library gets there by compacting the paged KV pool:
+ *
+ *   every live block whose physical id is at or above a reclaim boundary b is
+ *   moved into a free id below b - the k-th smallest moving id takes the k-th
+ *   smallest free id - the per-sequence block tables are rewritten, and the
+ *   new model's weights are streamed from pinned host memory into the byte
+ *   range that starts at block b.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is marked [device] or [host].  The library
+ *     allocates and frees nothing (except where a function says otherwise) and
+ *     owns nothing that outlives a call; the caller owns pool, tables, bitmap,
+ *     workspace, pinned host tensors, streams and events.
+ *   - `stream` / `event` arguments are hipStream_t / hipEvent_t passed as
+ *     void*; NULL stream = the default stream.
+ *   - Calls that take a stream are asynchronous on it and return after
+ *     enqueueing.  Return value: KV_OK or a negative KV_E_* for errors the host
+ *     can see (bad argument, failed launch).  Nothing is enqueued and no byte
+ *     is written when a call returns an error.
+ *   - The one data-dependent failure - more moving blocks than free ids below
+ *     the boundary - is recorded on the device in kv_plan_state.status.
+ *     kv_compact and kv_remap_tables read it and do nothing unless it is KV_OK,
+ *     so an infeasible request modifies no pool byte and no table entry
+ *     (existing requests take precedence over prewarmed weights, Sec. 3.3).
+ *   - Pool layout: one allocation, block-major.  Block i occupies bytes
+ *     [i*block_bytes, (i+1)*block_bytes), block_bytes = num_layers*tile_bytes;
+ *     within a block, layer l's K and V tile is tile_bytes bytes at l*tile_bytes.
+ *     Bytes are never interpreted (bf16 or fp8 alike).
+ *   - Re-entrant; no global state.  Two calls that touch the same plan or pool
+ *     must be ordered by the caller (same stream, or events).
+ */
+#ifndef WARMKV_H
+#define WARMKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KV_OK          0
+#define KV_E_NULL     (-1)  /* a required pointer is NULL                                  */
+#define KV_E_RANGE    (-2)  /* boundary > num_blocks, sizes that do not match the plan, ... */
+#define KV_E_ALIGN    (-3)  /* pool base not 256-byte aligned, tile_bytes not a multiple of 16 */
+#define KV_E_TOOBIG   (-4)  /* a weight extent leaves the reclaimed region; workspace too small */
+#define KV_E_OVERLAP  (-5)  /* two weight extents overlap; live_out aliases live_in          */
+#define KV_E_HIP      (-6)  /* a HIP call failed                                             */
+#define KV_E_NOSPACE  (-7)  /* device status: more movers than free ids below the boundary   */
+#define KV_E_BADPLAN  (-8)  /* device status: a move violates src >= boundary > dst          */
+
+/* Describes the caller-owned paged KV pool. */
+typedef struct kv_pool_desc {
+  void*    base;        /* [device] 256-byte aligned                                   */
+  uint32_t num_blocks;  /* NB, at most 2^24                                            */
+  uint32_t num_layers;  /* L >= 1                                                      */
+  uint64_t tile_bytes;  /* bytes of one block in one layer (K and V); multiple of 16   */
+} kv_pool_desc;
+
+/* Device-resident result header of a plan (16 bytes). */
+typedef struct kv_plan_state {
+  int32_t  status;         /* KV_OK, KV_E_NOSPACE or KV_E_BADPLAN                        */
+  uint32_t n_moves;        /* number of blocks to move (0 unless status == KV_OK)        */
+  uint32_t n_free_below;   /* free ids below the boundary before the move                */
+  uint32_t n_bad_entries;  /* table entries kv_remap_tables left alone (see there)       */
+} kv_plan_state;
+
+/* A relocation plan.  All pointers are [device] and point into the workspace
+ * the caller passed to kv_plan_bind. */
+typedef struct kv_plan {
+  int32_t*       src;        /* [capacity] moving ids, ascending; first n_moves valid    */
+  int32_t*       dst;        /* [capacity] destination ids, ascending, all < boundary    */
+  int32_t*       new_id;     /* [num_blocks] i -> id after the move, -1 for free ids     */
+  uint64_t*      live_out;   /* [ceil(num_blocks/64)] live bitmap after the move         */
+  kv_plan_state* state;
+  uint32_t       num_blocks;
+  uint32_t       boundary;   /* first reclaimed block id b                               */
+  uint32_t       capacity;   /* min(num_blocks - boundary, boundary)                     */
+  uint32_t       reserved;
+} kv_plan;
+
+/* Bytes of device workspace a plan for (num_blocks, boundary) needs; 0 if
+ * boundary > num_blocks. */
+size_t kv_plan_workspace_bytes(uint32_t num_blocks, uint32_t boundary);
+
+/* Carve `workspace` [device, 256-byte aligned, >= kv_plan_workspace_bytes()]
+ * into the arrays of `plan` [host].  Touches no device memory. */
+int kv_plan_bind(kv_plan* plan, void* workspace, size_t workspace_bytes,
+                 uint32_t num_blocks, uint32_t boundary);
+
+/* Relocation planner ("which physical blocks are unused, and where does each
+ * block that is in the way go": App. C, Fig. 4b step 1; how much to reclaim is
+ * Eq. 4's business and arrives as `boundary`).
+ * live_in [device]: uint64[ceil(NB/64)], bit (i%64) of word (i/64) set <=> block
+ * i holds live KV; bits at or beyond NB in the last word are ignored.  Must
+ * not overlap plan->live_out.
+ * Writes plan->state always; if feasible also src/dst[0..n_moves), new_id[NB]
+ * (identity for live ids < b, dst[k] for src[k], -1 for free ids) and live_out
+ * (bits >= b cleared, bits dst[0..n) set).  If infeasible: state.status =
+ * KV_E_NOSPACE, n_moves = 0, and the other outputs are unspecified. */
+int kv_plan_reclaim(const uint64_t* live_in, const kv_plan* plan, void* stream);
+
+/* Block copy: for k < n_moves, block dst[k] <- block src[k] (block_bytes each).
+ * Source blocks keep their bytes; no byte at or above block `boundary` and no
+ * byte of a non-destination block is written.  Does nothing unless
+ * state.status == KV_OK.  A move with src < boundary, src >= NB or dst >=
+ * boundary (possible only in a hand-built plan) is skipped and sets
+ * state.status = KV_E_BADPLAN.  pool->num_blocks must equal plan->num_blocks. */
+int kv_compact(const kv_pool_desc* pool, const kv_plan* plan, void* stream);
+
+/* Launch shape of kv_compact, for tuning.  Zero fields select the defaults. */
+typedef struct kv_compact_tuning {
+  uint32_t workgroups;     /* persistent grid size (default: 256 CUs x 8)               */
+  uint32_t chunk_bytes;    /* bytes one workgroup copies per step; multiple of 4096      */
+  uint32_t flags;          /* bit 0: plain (cached) instead of non-temporal accesses;
+                              bits 4-7: 128-bit loads in flight per lane (1, 2, 4 or 8)  */
+  uint32_t reserved;
+} kv_compact_tuning;
+
+/* kv_compact with an explicit launch shape (same results, same rules). */
+int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
+                      const kv_compact_tuning* tuning, void* stream);
+
+/* Block-table rewrite, run right after kv_compact on the same stream: every
+ * entry e >= 0 of tables [device, int32, num_seqs x max_blocks_per_seq,
+ * row-major, -1 = empty] becomes new_id[e].  Entries that name an id >= NB or
+ * a block that was not live are left as they are and counted in
+ * state.n_bad_entries (added to what is there).  Does nothing unless
+ * state.status == KV_OK.  (The engine goes on seeing one address space and
+ * never learns that blocks moved: App. C.) */
+int kv_remap_tables(int32_t* tables, uint32_t num_seqs, uint32_t max_blocks_per_seq,
+                    const kv_plan* plan, void* stream);
+
+/* Synchronise `stream` and copy the plan's header to `out` [host]. */
+int kv_plan_fetch(const kv_plan* plan, void* stream, kv_plan_state* out);
+
+/* One weight tensor: `bytes` bytes at host_ptr [host, pinned] go to byte
+ * offset dst_offset of the reclaimed region. */
+typedef struct wm_tensor {
+  const void* host_ptr;
+  uint64_t    bytes;
+  uint64_t    dst_offset;
+} wm_tensor;
+
+/* Weight materialisation ("the model's weights are then loaded into these
+ * pages", App. C, Fig. 4b step 3; host memory to GPU over the host link,
+ * Sec. 4.1; a copy is issued as soon as its destination is ready, App. C).
+ * The reclaimed region is bytes [boundary*block_bytes, num_blocks*block_bytes)
+ * of the pool.  All extents are validated first (inside the region: else
+ * KV_E_TOOBIG; pairwise disjoint: else KV_E_OVERLAP).  Then, on copy_stream:
+ * wait for `compaction_done` (hipEvent_t recorded after kv_compact; NULL = no
+ * wait, the caller has ordered the streams) and enqueue the host-to-device
+ * copies in chunks.  The region still holds moving blocks until kv_compact has
+ * read them, hence the event.  tensors [host] may be freed on return; the
+ * host_ptr buffers must stay valid until copy_stream has drained. */
+int weights_materialize(const kv_pool_desc* pool, uint32_t boundary,
+                        const wm_tensor* tensors, uint32_t n_tensors,
+                        void* copy_stream, void* compaction_done);
+
+/* Reserved KV space of a draining instance, Sec. 3.3 Eq. 4, in blocks:
+ * R = max(C*Q/B, T + C/B), fractional blocks rounded up, capped at C.
+ * C = capacity_blocks (<= 2^32 - 1), T = used_blocks, Q = running requests,
+ * B = max_batch.  The reclaim boundary is R.  Host arithmetic only.
+ * Returns R, or KV_E_RANGE if B == 0, T > C or C too large. */
+int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks,
+                          uint32_t running, uint32_t max_batch);
+
+/* Library version, "major.minor". */
+const char* warmkv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WARMKV_H */

@@ -146,12 +146,13 @@ int oracle_materialize(uint8_t* pool, uint64_t pool_bytes, uint64_t region_offse
 int64_t oracle_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks, uint32_t running,
                               uint32_t max_batch) {
   if (max_batch == 0 || used_blocks > capacity_blocks) return ORACLE_E_RANGE;
-  if (capacity_blocks > 0xFFFFFFFFull) return ORACLE_E_RANGE;  // keeps C*Q inside 64 bits
-  // ceil(max(x, y)) == max(ceil x, ceil y), and T is whole, so integers suffice.
-  const uint64_t C = capacity_blocks, B = max_batch;
-  const uint64_t by_requests = (C * running + B - 1) / B;
-  const uint64_t by_usage = used_blocks + (C + B - 1) / B;
-  uint64_t R = by_requests > by_usage ? by_requests : by_usage;
+  // Both targets over the common denominator B, maximum first, ceiling last.
+  const unsigned __int128 C = capacity_blocks, B = max_batch;
+  const unsigned __int128 by_requests = C * running;                       // (C*Q/B) * B
+  const unsigned __int128 by_usage = (unsigned __int128)used_blocks * B + C;  // (T + C/B) * B
+  const unsigned __int128 numerator = by_requests > by_usage ? by_requests : by_usage;
+  unsigned __int128 R = numerator / B;
+  if (R * B < numerator) ++R;
   if (R > C) R = C;
   return (int64_t)R;
 }

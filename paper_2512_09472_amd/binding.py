@@ -1,0 +1,173 @@
+"""ctypes binding of libwarmkv.so: the same names as the C ABI (include/warmkv.h),
+argument marshalling only.  Every step runs in the library's HIP kernels; there
+is no fallback: if the library is missing or was not built this module raises.
+
+Device and host buffers may be given as integers (raw addresses) or as any
+object with a ``data_ptr()`` method (torch tensors); streams and events as
+integers (``torch.cuda.Stream.cuda_stream``, ``torch.cuda.Event.cuda_event``)
+or 0 / None.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from ctypes import POINTER, Structure, byref, c_char_p, c_int, c_int32, c_int64, c_size_t, c_uint32, c_uint64, c_void_p
+
+from . import build as _build
+
+KV_OK = 0
+KV_E_NULL = -1
+KV_E_RANGE = -2
+KV_E_ALIGN = -3
+KV_E_TOOBIG = -4
+KV_E_OVERLAP = -5
+KV_E_HIP = -6
+KV_E_NOSPACE = -7
+KV_E_BADPLAN = -8
+
+_NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E_ALIGN: "KV_E_ALIGN",
+          KV_E_TOOBIG: "KV_E_TOOBIG", KV_E_OVERLAP: "KV_E_OVERLAP", KV_E_HIP: "KV_E_HIP",
+          KV_E_NOSPACE: "KV_E_NOSPACE", KV_E_BADPLAN: "KV_E_BADPLAN"}
+
+EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
+           "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "kv_reserve_blocks", "warmkv_version")
+
+
+class WarmKVError(RuntimeError):
+    def __init__(self, fn: str, code: int):
+        super().__init__(f"{fn} failed: {_NAMES.get(code, code)}")
+        self.code = code
+
+
+class kv_pool_desc(Structure):
+    _fields_ = [("base", c_void_p), ("num_blocks", c_uint32), ("num_layers", c_uint32), ("tile_bytes", c_uint64)]
+
+
+class kv_plan_state(Structure):
+    _fields_ = [("status", c_int32), ("n_moves", c_uint32), ("n_free_below", c_uint32), ("n_bad_entries", c_uint32)]
+
+
+class kv_plan(Structure):
+    _fields_ = [("src", c_void_p), ("dst", c_void_p), ("new_id", c_void_p), ("live_out", c_void_p),
+                ("state", c_void_p), ("num_blocks", c_uint32), ("boundary", c_uint32),
+                ("capacity", c_uint32), ("reserved", c_uint32)]
+
+
+class kv_compact_tuning(Structure):
+    _fields_ = [("workgroups", c_uint32), ("chunk_bytes", c_uint32), ("flags", c_uint32), ("reserved", c_uint32)]
+
+
+class wm_tensor(Structure):
+    _fields_ = [("host_ptr", c_void_p), ("bytes", c_uint64), ("dst_offset", c_uint64)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load():
+    """Load libwarmkv.so, building it first only if no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build()
+    L = ctypes.CDLL(_build.LIB_PATH)
+    L.kv_plan_workspace_bytes.restype = c_size_t
+    L.kv_plan_workspace_bytes.argtypes = [c_uint32, c_uint32]
+    L.kv_plan_bind.restype = c_int
+    L.kv_plan_bind.argtypes = [POINTER(kv_plan), c_void_p, c_size_t, c_uint32, c_uint32]
+    L.kv_plan_reclaim.restype = c_int
+    L.kv_plan_reclaim.argtypes = [c_void_p, POINTER(kv_plan), c_void_p]
+    L.kv_compact.restype = c_int
+    L.kv_compact.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), c_void_p]
+    L.kv_compact_launch.restype = c_int
+    L.kv_compact_launch.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), POINTER(kv_compact_tuning), c_void_p]
+    L.kv_remap_tables.restype = c_int
+    L.kv_remap_tables.argtypes = [c_void_p, c_uint32, c_uint32, POINTER(kv_plan), c_void_p]
+    L.kv_plan_fetch.restype = c_int
+    L.kv_plan_fetch.argtypes = [POINTER(kv_plan), c_void_p, POINTER(kv_plan_state)]
+    L.weights_materialize.restype = c_int
+    L.weights_materialize.argtypes = [POINTER(kv_pool_desc), c_uint32, POINTER(wm_tensor), c_uint32, c_void_p, c_void_p]
+    L.kv_reserve_blocks.restype = c_int64
+    L.kv_reserve_blocks.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
+    L.warmkv_version.restype = c_char_p
+    L.warmkv_version.argtypes = []
+    _lib = L
+    return L
+
+
+def _ptr(x) -> int | None:
+    if x is None:
+        return None
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr() or None
+    return int(x) or None
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != KV_OK:
+        raise WarmKVError(fn, rc)
+
+
+def pool_desc(base, num_blocks: int, num_layers: int, tile_bytes: int) -> kv_pool_desc:
+    return kv_pool_desc(_ptr(base), num_blocks, num_layers, tile_bytes)
+
+
+def kv_plan_workspace_bytes(num_blocks: int, boundary: int) -> int:
+    return int(load().kv_plan_workspace_bytes(num_blocks, boundary))
+
+
+def kv_plan_bind(workspace, workspace_bytes: int, num_blocks: int, boundary: int) -> kv_plan:
+    plan = kv_plan()
+    _check("kv_plan_bind", load().kv_plan_bind(byref(plan), _ptr(workspace), workspace_bytes, num_blocks, boundary))
+    return plan
+
+
+def kv_plan_reclaim(live_in, plan: kv_plan, stream=0) -> None:
+    _check("kv_plan_reclaim", load().kv_plan_reclaim(_ptr(live_in), byref(plan), _ptr(stream)))
+
+
+def kv_compact(pool: kv_pool_desc, plan: kv_plan, stream=0) -> None:
+    _check("kv_compact", load().kv_compact(byref(pool), byref(plan), _ptr(stream)))
+
+
+def kv_compact_launch(pool: kv_pool_desc, plan: kv_plan, stream=0, *, workgroups: int = 0,
+                      chunk_bytes: int = 0, flags: int = 0) -> None:
+    t = kv_compact_tuning(workgroups, chunk_bytes, flags, 0)
+    _check("kv_compact_launch", load().kv_compact_launch(byref(pool), byref(plan), byref(t), _ptr(stream)))
+
+
+def kv_remap_tables(tables, num_seqs: int, max_blocks_per_seq: int, plan: kv_plan, stream=0) -> None:
+    _check("kv_remap_tables", load().kv_remap_tables(_ptr(tables), num_seqs, max_blocks_per_seq, byref(plan),
+                                                      _ptr(stream)))
+
+
+def kv_plan_fetch(plan: kv_plan, stream=0) -> kv_plan_state:
+    out = kv_plan_state()
+    _check("kv_plan_fetch", load().kv_plan_fetch(byref(plan), _ptr(stream), byref(out)))
+    return out
+
+
+def weights_materialize(pool: kv_pool_desc, boundary: int, tensors, copy_stream=0, compaction_done=None) -> None:
+    """tensors: iterable of (host buffer or address, bytes, dst_offset)."""
+    items = list(tensors)
+    arr = (wm_tensor * max(1, len(items)))()
+    for i, (host, nbytes, off) in enumerate(items):
+        arr[i] = wm_tensor(_ptr(host), nbytes, off)
+    _check("weights_materialize", load().weights_materialize(byref(pool), boundary, arr, len(items),
+                                                              _ptr(copy_stream), _ptr(compaction_done)))
+
+
+def kv_reserve_blocks(capacity_blocks: int, used_blocks: int, running: int, max_batch: int) -> int:
+    r = int(load().kv_reserve_blocks(capacity_blocks, used_blocks, running, max_batch))
+    if r < 0:
+        raise WarmKVError("kv_reserve_blocks", r)
+    return r
+
+
+def warmkv_version() -> str:
+    return load().warmkv_version().decode()

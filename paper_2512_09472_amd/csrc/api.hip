@@ -1,0 +1,75 @@
+// Host-side pieces of the C ABI that launch nothing: workspace layout, plan
+// binding, result fetch, the reservation formula and the version string.
+#include "common.h"
+
+namespace warmkv {
+namespace {
+
+struct Layout {
+  size_t state, live_out, src, dst, new_id, total;
+};
+
+// state | live_out | src | dst | new_id, each segment 256-byte aligned
+Layout layout(uint32_t num_blocks, uint32_t boundary) {
+  const size_t n_words = ((size_t)num_blocks + 63) / 64;
+  const size_t cap = num_blocks - boundary < boundary ? num_blocks - boundary : boundary;
+  Layout l;
+  l.state = 0;
+  l.live_out = 256;
+  l.src = l.live_out + align_up(n_words * 8, 256);
+  l.dst = l.src + align_up(cap * 4, 256);
+  l.new_id = l.dst + align_up(cap * 4, 256);
+  l.total = l.new_id + align_up((size_t)num_blocks * 4, 256);
+  return l;
+}
+
+}  // namespace
+}  // namespace warmkv
+
+using namespace warmkv;
+
+extern "C" size_t kv_plan_workspace_bytes(uint32_t num_blocks, uint32_t boundary) {
+  if (boundary > num_blocks || num_blocks > kMaxBlocks) return 0;
+  return layout(num_blocks, boundary).total;
+}
+
+extern "C" int kv_plan_bind(kv_plan* plan, void* workspace, size_t workspace_bytes, uint32_t num_blocks,
+                            uint32_t boundary) {
+  if (plan == nullptr || workspace == nullptr) return KV_E_NULL;
+  if (boundary > num_blocks || num_blocks > kMaxBlocks) return KV_E_RANGE;
+  if (((uintptr_t)workspace % 256u) != 0) return KV_E_ALIGN;
+  const Layout l = layout(num_blocks, boundary);
+  if (workspace_bytes < l.total) return KV_E_TOOBIG;
+  uint8_t* w = (uint8_t*)workspace;
+  plan->state = (kv_plan_state*)(w + l.state);
+  plan->live_out = (uint64_t*)(w + l.live_out);
+  plan->src = (int32_t*)(w + l.src);
+  plan->dst = (int32_t*)(w + l.dst);
+  plan->new_id = (int32_t*)(w + l.new_id);
+  plan->num_blocks = num_blocks;
+  plan->boundary = boundary;
+  plan->capacity = num_blocks - boundary < boundary ? num_blocks - boundary : boundary;
+  plan->reserved = 0;
+  return KV_OK;
+}
+
+extern "C" int kv_plan_fetch(const kv_plan* plan, void* stream, kv_plan_state* out) {
+  if (plan == nullptr || plan->state == nullptr || out == nullptr) return KV_E_NULL;
+  hipStream_t s = (hipStream_t)stream;
+  int rc = hip_rc(hipMemcpyAsync(out, plan->state, sizeof(kv_plan_state), hipMemcpyDeviceToHost, s));
+  if (rc != KV_OK) return rc;
+  return hip_rc(hipStreamSynchronize(s));
+}
+
+// Sec. 3.3, Eq. 4: R = max(C*Q/B, T + C/B).  The ceiling of a maximum is the
+// maximum of the ceilings and T is whole, so integer arithmetic is exact.
+extern "C" int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks, uint32_t running,
+                                     uint32_t max_batch) {
+  if (max_batch == 0 || used_blocks > capacity_blocks || capacity_blocks > 0xFFFFFFFFull) return KV_E_RANGE;
+  const uint64_t expected = (capacity_blocks * running + max_batch - 1) / max_batch;
+  const uint64_t headroom = used_blocks + (capacity_blocks + max_batch - 1) / max_batch;
+  const uint64_t r = expected > headroom ? expected : headroom;
+  return (int64_t)(r > capacity_blocks ? capacity_blocks : r);
+}
+
+extern "C" const char* warmkv_version(void) { return "0.1"; }

@@ -1,0 +1,130 @@
+"""Host-only checks of the C ABI: the library loads, exports what the header
+declares, and rejects bad arguments before touching the device.  No GPU needed:
+every call here returns before its first HIP call."""
+import ctypes
+import json
+import os
+import re
+
+import pytest
+
+import paper_2512_09472_amd as wk
+from paper_2512_09472_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000   # an aligned address that is never dereferenced
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "warmkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_][a-z0-9_]*)\s*\([^;{}]*\)\s*;", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_functions()
+    assert set(names) == set(binding.EXPORTS), names
+    lib = ctypes.CDLL(binding.library_path()) if os.path.exists(binding.library_path()) else binding.load()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert wk.warmkv_version() == "0.1"
+
+
+def test_struct_sizes_match_the_header():
+    assert ctypes.sizeof(binding.kv_pool_desc) == 24
+    assert ctypes.sizeof(binding.kv_plan_state) == 16
+    assert ctypes.sizeof(binding.kv_plan) == 56
+    assert ctypes.sizeof(binding.kv_compact_tuning) == 16
+    assert ctypes.sizeof(binding.wm_tensor) == 24
+
+
+def test_workspace_and_bind():
+    nb, b = 20480, 12288
+    need = wk.kv_plan_workspace_bytes(nb, b)
+    cap = min(nb - b, b)
+    assert need >= 16 + nb // 8 + 8 * cap + 4 * nb and need % 256 == 0
+    assert wk.kv_plan_workspace_bytes(10, 11) == 0
+    assert wk.kv_plan_workspace_bytes((1 << 24) + 1, 0) == 0
+    p = wk.kv_plan_bind(FAKE, need, nb, b)
+    assert (p.num_blocks, p.boundary, p.capacity) == (nb, b, cap)
+    segs = sorted([(p.state, 16), (p.live_out, nb // 8), (p.src, 4 * cap), (p.dst, 4 * cap), (p.new_id, 4 * nb)])
+    for (a, n), (a2, _) in zip(segs, segs[1:]):
+        assert a + n <= a2 and a % 256 == 0
+    assert segs[0][0] == FAKE and segs[-1][0] + segs[-1][1] <= FAKE + need
+    for args, code in (((FAKE, need - 1, nb, b), wk.KV_E_TOOBIG), ((FAKE + 8, need, nb, b), wk.KV_E_ALIGN),
+                       ((0, need, nb, b), wk.KV_E_NULL), ((FAKE, need, nb, nb + 1), wk.KV_E_RANGE)):
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.kv_plan_bind(*args)
+        assert e.value.code == code
+
+
+def test_calls_reject_bad_arguments_before_any_launch():
+    nb, b = 1024, 512
+    plan = wk.kv_plan_bind(FAKE, wk.kv_plan_workspace_bytes(nb, b), nb, b)
+    pool = wk.pool_desc(FAKE + (1 << 30), nb, 1, 65536)
+
+    def code(fn, *a, **k):
+        with pytest.raises(wk.WarmKVError) as e:
+            fn(*a, **k)
+        return e.value.code
+
+    assert code(wk.kv_plan_reclaim, 0, plan) == wk.KV_E_NULL
+    assert code(wk.kv_plan_reclaim, plan.live_out, plan) == wk.KV_E_OVERLAP
+    assert code(wk.kv_plan_reclaim, plan.live_out + 8, plan) == wk.KV_E_OVERLAP
+    bad = wk.kv_plan_bind(FAKE, wk.kv_plan_workspace_bytes(nb, b), nb, b)
+    bad.boundary = nb + 1
+    assert code(wk.kv_plan_reclaim, FAKE + (1 << 20), bad) == wk.KV_E_RANGE
+    assert code(wk.kv_compact, pool, bad) == wk.KV_E_RANGE
+    assert code(wk.kv_remap_tables, FAKE + (1 << 20), 4, 4, bad) == wk.KV_E_RANGE
+    assert code(wk.kv_compact, wk.pool_desc(FAKE, nb + 1, 1, 65536), plan) == wk.KV_E_RANGE
+    assert code(wk.kv_compact, wk.pool_desc(FAKE, nb, 1, 65528), plan) == wk.KV_E_ALIGN
+    assert code(wk.kv_compact, wk.pool_desc(FAKE + 16, nb, 1, 65536), plan) == wk.KV_E_ALIGN
+    assert code(wk.kv_compact, wk.pool_desc(0, nb, 1, 65536), plan) == wk.KV_E_NULL
+    assert code(wk.kv_compact, wk.pool_desc(FAKE, nb, 0, 65536), plan) == wk.KV_E_RANGE
+    assert code(wk.kv_compact_launch, pool, plan, chunk_bytes=1000) == wk.KV_E_RANGE
+    assert code(wk.kv_compact_launch, pool, plan, flags=3 << 4) == wk.KV_E_RANGE
+    assert code(wk.kv_remap_tables, 0, 4, 4, plan) == wk.KV_E_NULL
+    assert code(wk.kv_remap_tables, FAKE + 4, 4, 4, plan) == wk.KV_E_ALIGN
+    wk.kv_remap_tables(0, 0, 128, plan)          # no entries: nothing to do, no launch
+
+
+def test_materialize_validates_every_extent_first():
+    nb, b, tile = 64, 40, 4096
+    pool = wk.pool_desc(FAKE, nb, 2, tile)
+    region = (nb - b) * 2 * tile
+
+    def code(tensors, boundary=b):
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.weights_materialize(pool, boundary, tensors)
+        return e.value.code
+
+    assert code([(FAKE, 16, 0), (FAKE, region, 1)]) == wk.KV_E_TOOBIG
+    assert code([(FAKE, 16, region - 15)]) == wk.KV_E_TOOBIG
+    assert code([(FAKE, 16, region + 1)]) == wk.KV_E_TOOBIG
+    assert code([(FAKE, 32, 0), (FAKE, 32, 64), (FAKE, 1, 95)]) == wk.KV_E_OVERLAP
+    assert code([(FAKE, 32, 64), (FAKE, 65, 0)]) == wk.KV_E_OVERLAP
+    assert code([(0, 32, 0)]) == wk.KV_E_NULL
+    assert code([(FAKE, 32, 0)], boundary=nb + 1) == wk.KV_E_RANGE
+    wk.weights_materialize(pool, b, [])                       # nothing to copy
+    wk.weights_materialize(pool, b, [(0, 0, 5), (0, 0, 5)])   # empty extents never overlap
+
+
+def test_reserve_blocks_matches_eq4_fixtures():
+    with open(os.path.join(ROOT, "tests", "golden", "eq4_reserve.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        assert wk.kv_reserve_blocks(c["C"], c["T"], c["Q"], c["B"]) == c["R"], c["note"]
+    for args in ((10, 11, 1, 32), (10, 1, 1, 0), (1 << 33, 1, 1, 2)):
+        with pytest.raises(wk.WarmKVError):
+            wk.kv_reserve_blocks(*args)
+
+
+def test_reserve_blocks_matches_oracle(oracle):
+    from synth.rng import SplitMix64
+    rng = SplitMix64(99)
+    for _ in range(3000):
+        C = rng.randint(1, 1 << 22)
+        T = rng.randint(0, C)
+        B = rng.randint(1, 512)
+        Q = rng.randint(0, B + 3)
+        assert wk.kv_reserve_blocks(C, T, Q, B) == oracle.reserve_blocks(C, T, Q, B)

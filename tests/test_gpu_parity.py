@@ -1,0 +1,280 @@
+"""GPU parity: the HIP path through the C ABI against the CPU oracle, element
+by element, on the same seeded inputs.  Integer and byte work: the bar is
+bit-exact (no tolerance exists on this path)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import gpu_harness as gh                      # noqa: E402
+import paper_2512_09472_amd as wk             # noqa: E402
+from synth import CONFIGS, bitmap_from_ids, content, make_workload   # noqa: E402
+from synth.rng import SplitMix64              # noqa: E402
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    wk.binding.load()
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _compare_plan(dp, p):
+    st, src, dst, new_id, live_out = dp.results()
+    assert st.status == p.status
+    if p.status != 0:
+        assert st.n_moves == 0
+        return st
+    assert st.n_moves == p.n_moves
+    assert np.array_equal(src, p.src), "src"
+    assert np.array_equal(dst, p.dst), "dst"
+    assert np.array_equal(new_id, p.new_id), "new_id"
+    assert np.array_equal(live_out, p.live_out), "live_out"
+    return st
+
+
+SCALED = {
+    "cfg1_tiny": CONFIGS[0],
+    "cfg2_small": CONFIGS[1].scaled(num_blocks=640, num_layers=3, num_seqs=40),
+    "cfg2_ragged_tile": CONFIGS[1].scaled(num_blocks=900, num_layers=5, kv_heads=3, head_dim=40, num_seqs=40),
+    "cfg4_odd_boundary": CONFIGS[3].scaled(num_blocks=1536, num_layers=4, num_seqs=128),
+    "cfg5_frag": CONFIGS[4].scaled(num_blocks=4096, num_layers=2, num_seqs=1024),
+    "cfg5_tiny_tile": CONFIGS[4].scaled(num_blocks=2048, num_layers=1, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512),
+}
+
+TUNINGS = [None,
+           dict(chunk_bytes=4096, flags=1 << 4),
+           dict(chunk_bytes=65536, flags=(8 << 4) | 1),
+           dict(workgroups=7, chunk_bytes=8192, flags=2 << 4),
+           dict(workgroups=5000, chunk_bytes=32768, flags=4 << 4)]
+
+
+@pytest.mark.parametrize("name", list(SCALED))
+def test_reclaim_matches_oracle(oracle, name):
+    cfg = SCALED[name]
+    w = make_workload(cfg)
+    table = gh.content_table(cfg)
+    pool0 = gh.host_pool(cfg, table)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    assert p.status == 0 and p.n_moves > 0
+    want_pool = pool0.copy()
+    oracle.compact(want_pool, cfg.block_bytes, p)
+    want_tables = w.tables.copy()
+    assert oracle.remap(want_tables, p) == 0
+    for tuning in TUNINGS:
+        _say(f"[parity] {name} block_bytes={cfg.block_bytes} NB={cfg.num_blocks} b={cfg.boundary} tuning={tuning}")
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        dp, tables_dev = gh.run_reclaim(cfg, w.live, w.tables, pool_dev, tuning=tuning)
+        st = _compare_plan(dp, p)
+        assert st.n_bad_entries == 0
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), "tables"
+        got = pool_dev.cpu().numpy()
+        if not np.array_equal(got, want_pool):
+            bad = np.flatnonzero(got.reshape(cfg.num_blocks, -1) != want_pool.reshape(cfg.num_blocks, -1))[:5]
+            pytest.fail(f"pool differs, first flat positions {bad}")
+        del pool_dev
+
+
+def test_device_fill_matches_host_generator():
+    for cfg in (SCALED["cfg2_ragged_tile"], SCALED["cfg5_frag"].scaled(num_blocks=64)):
+        table = gh.content_table(cfg)
+        n = min(cfg.num_blocks, 48)
+        cids = np.array([(7 * i + 3) % 100000 for i in range(n)], dtype=np.int32)
+        want = np.empty(n * cfg.block_bytes, dtype=np.uint8)
+        content.fill_host(want, cfg.block_bytes, cids, cfg.seed, table)
+        buf = torch.zeros(n * cfg.block_bytes, dtype=torch.uint8, device=gh.dev())
+        tdev = gh.to_dev(table) if table is not None else None
+        content.fill_device(buf.data_ptr(), n, cfg.block_bytes, cfg.seed, cids_ptr=gh.to_dev(cids).data_ptr(),
+                            table_ptr=tdev.data_ptr() if tdev is not None else 0)
+        torch.cuda.synchronize()
+        assert np.array_equal(buf.cpu().numpy(), want)
+        content.fill_device(buf.data_ptr(), n, cfg.block_bytes, cfg.seed, cid0=11,
+                            table_ptr=tdev.data_ptr() if tdev is not None else 0)
+        torch.cuda.synchronize()
+        content.fill_host(want, cfg.block_bytes, range(11, 11 + n), cfg.seed, table)
+        assert np.array_equal(buf.cpu().numpy(), want)
+
+
+PLAN_CASES = [(1, 0, 1.0), (1, 1, 1.0), (63, 31, 0.4), (64, 64, 0.3), (65, 64, 0.5), (130, 70, 0.3),
+              (1000, 999, 0.5), (4097, 2500, 0.5), (65536, 32768, 0.45), (65536, 65535, 0.5),
+              (65537, 40001, 0.5), (70001, 33333, 0.4), (200000, 131072, 0.6), (200000, 77777, 0.35),
+              (300000, 0, 0.0), (300000, 300000, 0.7), (1 << 20, 600011, 0.5)]
+
+
+@pytest.mark.parametrize("nb,b,p_live", PLAN_CASES)
+def test_planner_matches_oracle(oracle, nb, b, p_live):
+    rs = np.random.default_rng(nb * 7 + b)
+    for trial in range(2):
+        live_bits = rs.random(nb) < p_live
+        if trial == 1 and nb > 2:
+            live_bits[max(0, b - 1)] = True
+            live_bits[min(nb - 1, b)] = True
+        live = bitmap_from_ids(np.flatnonzero(live_bits), nb)
+        if nb % 64:
+            live[-1] |= np.uint64(0xFFFFFFFFFFFFFFFF) << np.uint64(nb % 64)   # junk past NB must be ignored
+        p = oracle.plan(bitmap_from_ids(np.flatnonzero(live_bits), nb), nb, b)
+        _say(f"[plan] NB={nb} b={b} p={p_live} trial={trial} oracle_status={p.status} n={p.n_moves}")
+        dp = gh.DevicePlan(nb, b)
+        live_dev = gh.to_dev(live)
+        wk.kv_plan_reclaim(live_dev, dp.plan)
+        st = _compare_plan(dp, p)
+        free_below = int((~live_bits[:b]).sum())
+        assert st.n_free_below == free_below
+
+
+def test_planner_on_handworked_fixtures():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "plan_handworked.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        nb, b = c["num_blocks"], c["boundary"]
+        live = np.array([int(h, 16) for h in c["live_words_hex"]], dtype=np.uint64)
+        dp = gh.DevicePlan(nb, b)
+        wk.kv_plan_reclaim(gh.to_dev(live), dp.plan)
+        st, src, dst, new_id, live_out = dp.results()
+        assert st.status == c["status"], c["name"]
+        if c["status"] != 0:
+            continue
+        assert src.tolist() == c["src"] and dst.tolist() == c["dst"], c["name"]
+        if "new_id" in c:
+            assert new_id.tolist() == c["new_id"]
+        assert [f"{int(x):016x}" for x in live_out] == c["live_out_words_hex"]
+        t = torch.tensor(c["tables_before"], dtype=torch.int32, device=gh.dev())
+        wk.kv_remap_tables(t, t.shape[0], t.shape[1], dp.plan)
+        torch.cuda.synchronize()
+        assert t.cpu().tolist() == c["tables_after"], c["name"]
+
+
+def test_infeasible_request_modifies_nothing(oracle):
+    """The config's literal 70 % occupancy does not fit under its own boundary."""
+    cfg = CONFIGS[1].scaled(num_blocks=2048, num_layers=2, num_seqs=64,
+                            live_budget_override=int(0.7 * 2048))
+    w = make_workload(cfg)
+    assert w.live_count > cfg.boundary
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    assert p.status == oracle.E_NOSPACE
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    dp, tables_dev = gh.run_reclaim(cfg, w.live, w.tables, pool_dev)
+    st = dp.state()
+    assert st.status == wk.KV_E_NOSPACE and st.n_moves == 0
+    assert np.array_equal(pool_dev.cpu().numpy(), pool0)
+    assert np.array_equal(tables_dev.cpu().numpy(), w.tables)
+    # one block fewer than the threshold fits exactly
+    ids = SplitMix64(4).shuffle(cfg.num_blocks)
+    for live_count, ok in ((cfg.boundary, True), (cfg.boundary + 1, False)):
+        live = bitmap_from_ids(ids[:live_count], cfg.num_blocks)
+        dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+        wk.kv_plan_reclaim(gh.to_dev(live), dp.plan)
+        torch.cuda.synchronize()
+        assert (dp.state().status == 0) == ok
+        _compare_plan(dp, oracle.plan(live, cfg.num_blocks, cfg.boundary))
+
+
+def test_bad_table_entries_are_counted_and_left(oracle):
+    nb, b = 300, 160
+    rs = np.random.default_rng(5)
+    live_bits = rs.random(nb) < 0.4
+    live = bitmap_from_ids(np.flatnonzero(live_bits), nb)
+    p = oracle.plan(live, nb, b)
+    assert p.status == 0
+    t = rs.integers(-1, nb + 40, size=(37, 11)).astype(np.int32)   # many entries name free or outside ids
+    want = t.copy()
+    bad = oracle.remap(want, p)
+    assert bad > 0
+    dp = gh.DevicePlan(nb, b)
+    wk.kv_plan_reclaim(gh.to_dev(live), dp.plan)
+    td = torch.from_numpy(t).to(gh.dev())
+    wk.kv_remap_tables(td, t.shape[0], t.shape[1], dp.plan)
+    torch.cuda.synchronize()
+    assert np.array_equal(td.cpu().numpy(), want)
+    assert dp.state().n_bad_entries == bad
+
+
+def test_remap_table_shapes(oracle):
+    """Entry counts around the 4-wide vector path, including odd tails."""
+    nb, b = 5000, 2600
+    rs = np.random.default_rng(8)
+    live_bits = rs.random(nb) < 0.45
+    ids = np.flatnonzero(live_bits)
+    live = bitmap_from_ids(ids, nb)
+    p = oracle.plan(live, nb, b)
+    dp = gh.DevicePlan(nb, b)
+    wk.kv_plan_reclaim(gh.to_dev(live), dp.plan)
+    for rows, cols in ((1, 1), (1, 3), (3, 5), (7, 4), (64, 128), (129, 33), (8192, 16), (5, 2048)):
+        t = rs.choice(np.concatenate([ids, np.full(ids.size // 3, -1)]), size=(rows, cols)).astype(np.int32)
+        want = t.copy()
+        assert oracle.remap(want, p) == 0
+        td = torch.from_numpy(t).to(gh.dev())
+        wk.kv_remap_tables(td, rows, cols, dp.plan)
+        torch.cuda.synchronize()
+        assert np.array_equal(td.cpu().numpy(), want), (rows, cols)
+    assert dp.state().n_bad_entries == 0
+
+
+def test_hand_built_bad_plan_is_refused_per_move():
+    """A move that breaks src >= boundary > dst is skipped and flagged; valid moves still run."""
+    cfg = CONFIGS[0].scaled(num_blocks=64, boundary=32)
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    live = bitmap_from_ids([40, 50], cfg.num_blocks)
+    wk.kv_plan_reclaim(gh.to_dev(live), dp.plan)
+    torch.cuda.synchronize()
+    assert dp.state().n_moves == 2
+    # overwrite the lists by hand: first move valid (40 -> 0), second invalid (10 -> 50)
+    dp._slice(dp.plan.src, 8).copy_(gh.to_dev(np.array([40, 10], dtype=np.int32)))
+    dp._slice(dp.plan.dst, 8).copy_(gh.to_dev(np.array([0, 50], dtype=np.int32)))
+    wk.kv_compact(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes), dp.plan)
+    torch.cuda.synchronize()
+    assert dp.state().status == wk.KV_E_BADPLAN
+    got = pool_dev.cpu().numpy().reshape(cfg.num_blocks, -1)
+    want = pool0.reshape(cfg.num_blocks, -1).copy()
+    want[0] = want[40]
+    assert np.array_equal(got, want)
+
+
+def test_materialize_matches_oracle_and_overlaps_compaction(oracle):
+    """Weights land byte-exactly in the reclaimed region, with the copy stream
+    gated on the compaction event; bytes outside every extent keep their value."""
+    cfg = CONFIGS[2].scaled(num_blocks=512, num_layers=4, num_seqs=48)
+    w = make_workload(cfg)
+    table = gh.content_table(cfg)
+    pool0 = gh.host_pool(cfg, table)
+    region_bytes = (cfg.num_blocks - cfg.boundary) * cfg.block_bytes
+    wtable = content.normal_bf16_table(0.02)
+    sizes = [3 * 4096 * 2, 1024 * 512 * 2, 256, 7 * 16, 5 * (1 << 20)]
+    offs = [0, 3 * 4096 * 2, 40 << 20, (40 << 20) + 256, region_bytes - 5 * (1 << 20)]
+    hosts = []
+    for i, sz in enumerate(sizes):
+        h = torch.empty(sz, dtype=torch.uint8, pin_memory=True)
+        h.numpy()[:] = content.item_bytes_host(0xBEEF, i, -(-sz // 8) * 8, wtable)[:sz]
+        hosts.append(h)
+    # oracle
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want = pool0.copy()
+    oracle.compact(want, cfg.block_bytes, p)
+    assert oracle.materialize(want, cfg.boundary * cfg.block_bytes,
+                              [(h.numpy(), o) for h, o in zip(hosts, offs)]) == 0
+    # device: compaction on one stream, copies on another, event in between
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    live_dev = gh.to_dev(w.live)
+    s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+    done = torch.cuda.Event()
+    torch.cuda.synchronize()
+    wk.kv_plan_reclaim(live_dev, dp.plan, s_compute.cuda_stream)
+    wk.kv_compact(pool, dp.plan, s_compute.cuda_stream)
+    done.record(s_compute)
+    wk.weights_materialize(pool, cfg.boundary, [(h, h.numel(), o) for h, o in zip(hosts, offs)],
+                           s_copy.cuda_stream, done.cuda_event)
+    torch.cuda.synchronize()
+    assert np.array_equal(pool_dev.cpu().numpy(), want)

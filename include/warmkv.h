@@ -65,12 +65,15 @@ typedef struct kv_pool_desc {
   uint64_t tile_bytes;  /* bytes of one block in one layer (K and V); multiple of 16   */
 } kv_pool_desc;
 
-/* Device-resident result header of a plan (16 bytes). */
+/* Device-resident result header of a plan (32 bytes). */
 typedef struct kv_plan_state {
   int32_t  status;         /* KV_OK, KV_E_NOSPACE or KV_E_BADPLAN                        */
   uint32_t n_moves;        /* number of blocks to move (0 unless status == KV_OK)        */
   uint32_t n_free_below;   /* free ids below the boundary before the move                */
   uint32_t n_bad_entries;  /* table entries kv_remap_tables left alone (see there)       */
+  uint32_t ticket;         /* kv_compact's work counter; zero between calls              */
+  uint32_t finished;       /* kv_compact's exit counter; zero between calls              */
+  uint32_t reserved[2];
 } kv_plan_state;
 
 /* A relocation plan.  All pointers are [device] and point into the workspace
@@ -113,14 +116,18 @@ int kv_plan_reclaim(const uint64_t* live_in, const kv_plan* plan, void* stream);
  * byte of a non-destination block is written.  Does nothing unless
  * state.status == KV_OK.  A move with src < boundary, src >= NB or dst >=
  * boundary (possible only in a hand-built plan) is skipped and sets
- * state.status = KV_E_BADPLAN.  pool->num_blocks must equal plan->num_blocks. */
+ * state.status = KV_E_BADPLAN.  pool->num_blocks must equal plan->num_blocks.
+ * Uses state.ticket / state.finished as scratch counters (zeroed by the
+ * planner, left at zero on exit): two kv_compact calls on one plan must not
+ * overlap in time. */
 int kv_compact(const kv_pool_desc* pool, const kv_plan* plan, void* stream);
 
 /* Launch shape of kv_compact, for tuning.  Zero fields select the defaults. */
 typedef struct kv_compact_tuning {
-  uint32_t workgroups;     /* persistent grid size (default: 256 CUs x 8)               */
-  uint32_t chunk_bytes;    /* bytes one workgroup copies per step; multiple of 4096      */
+  uint32_t workgroups;     /* persistent grid size (default: one per compute unit)       */
+  uint32_t chunk_bytes;    /* bytes per work ticket; multiple of 4096 (default 65536)    */
   uint32_t flags;          /* bit 0: plain (cached) instead of non-temporal accesses;
+                              bit 1: static grid-stride order instead of tickets;
                               bits 4-7: 128-bit loads in flight per lane (1, 2, 4 or 8)  */
   uint32_t reserved;
 } kv_compact_tuning;

@@ -44,7 +44,8 @@ class kv_pool_desc(Structure):
 
 
 class kv_plan_state(Structure):
-    _fields_ = [("status", c_int32), ("n_moves", c_uint32), ("n_free_below", c_uint32), ("n_bad_entries", c_uint32)]
+    _fields_ = [("status", c_int32), ("n_moves", c_uint32), ("n_free_below", c_uint32), ("n_bad_entries", c_uint32),
+                ("ticket", c_uint32), ("finished", c_uint32), ("reserved", c_uint32 * 2)]
 
 
 class kv_plan(Structure):

@@ -131,6 +131,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     st.n_moves = feasible ? n_moves : 0u;
     st.n_free_below = n_avail;
     st.n_bad_entries = 0u;
+    st.ticket = 0u;
+    st.finished = 0u;
+    st.reserved[0] = st.reserved[1] = 0u;
     *state = st;
   }
   if (!feasible) return;  // uniform over the whole grid: nothing else is written

@@ -48,11 +48,13 @@ SCALED = {
     "cfg5_tiny_tile": CONFIGS[4].scaled(num_blocks=2048, num_layers=1, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512),
 }
 
-TUNINGS = [None,
+TUNINGS = [None,                                                        # defaults: tickets, 64 KiB, one WG per CU
            dict(chunk_bytes=4096, flags=1 << 4),
-           dict(chunk_bytes=65536, flags=(8 << 4) | 1),
+           dict(chunk_bytes=65536, flags=(8 << 4) | 1),                 # cached accesses
            dict(workgroups=7, chunk_bytes=8192, flags=2 << 4),
-           dict(workgroups=5000, chunk_bytes=32768, flags=4 << 4)]
+           dict(workgroups=3000, chunk_bytes=32768, flags=4 << 4),      # more workgroups than fit at once
+           dict(workgroups=5000, chunk_bytes=32768, flags=(4 << 4) | 2),   # static grid-stride order
+           dict(workgroups=256, chunk_bytes=1 << 20, flags=(2 << 4) | 2)]
 
 
 @pytest.mark.parametrize("name", list(SCALED))
@@ -73,6 +75,7 @@ def test_reclaim_matches_oracle(oracle, name):
         dp, tables_dev = gh.run_reclaim(cfg, w.live, w.tables, pool_dev, tuning=tuning)
         st = _compare_plan(dp, p)
         assert st.n_bad_entries == 0
+        assert st.ticket == 0 and st.finished == 0, "work counters must return to zero"
         assert np.array_equal(tables_dev.cpu().numpy(), want_tables), "tables"
         got = pool_dev.cpu().numpy()
         if not np.array_equal(got, want_pool):
@@ -234,7 +237,8 @@ def test_hand_built_bad_plan_is_refused_per_move():
     dp._slice(dp.plan.dst, 8).copy_(gh.to_dev(np.array([0, 50], dtype=np.int32)))
     wk.kv_compact(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes), dp.plan)
     torch.cuda.synchronize()
-    assert dp.state().status == wk.KV_E_BADPLAN
+    st = dp.state()
+    assert st.status == wk.KV_E_BADPLAN and st.ticket == 0 and st.finished == 0
     got = pool_dev.cpu().numpy().reshape(cfg.num_blocks, -1)
     want = pool0.reshape(cfg.num_blocks, -1).copy()
     want[0] = want[40]

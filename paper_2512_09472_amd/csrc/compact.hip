@@ -153,7 +153,8 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
   }
   if ((chunk % kRowBytes) != 0 || workgroups > (1u << 20)) return KV_E_RANGE;
   const uint32_t unroll_sel = (flags >> 4) & 0xFu;  // 0 = pick from the chunk size
-  const uint32_t unroll = unroll_sel ? unroll_sel : (chunk >= 4 * kRowBytes ? 4u : (chunk >= 2 * kRowBytes ? 2u : 1u));
+  const uint32_t unroll = unroll_sel ? unroll_sel
+                                     : (chunk >= 8 * kRowBytes ? 8u : (chunk >= 4 * kRowBytes ? 4u : (chunk >= 2 * kRowBytes ? 2u : 1u)));
   if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return KV_E_RANGE;
 
   if (plan->capacity == 0 || pool->num_blocks == 0) return KV_OK;  // nothing can move

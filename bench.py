@@ -32,6 +32,12 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
 LINK_PEAK_GBPS = 63.0           # PCIe 5.0 x16, one direction, theoretical
 
+# HBM bytes per launch of the block-copy kernel from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE, each scaled by what the counter shows for a plain 1 GiB copy: x2.0 and x1.0), for
+# configs[1] with the default launch shape.  Profiler figures cannot be taken inside this
+# process; other workloads or launch shapes report null.
+MEASURED_TRAFFIC_BYTES = {(1, 4687): 19_664_169_678}
+
 
 def parse_args():
     ap = argparse.ArgumentParser()
@@ -185,7 +191,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "compact_ticket_kernel",
                      "achieved": round(rw_bytes / (compact_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(rw_bytes / (compact_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "traffic": None,
+                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.index, n_moves)) if not any(tuning.values()) else None,
                      "kernel_ms_avg": round(compact_avg, 4), "kernel_ms_min": round(min(compact_ms), 4),
                      "kernel_ms_median": round(statistics.median(compact_ms), 4),
                      "algorithmic_bytes_per_launch": rw_bytes},

@@ -172,6 +172,42 @@ int weights_materialize(const kv_pool_desc* pool, uint32_t boundary,
                         const wm_tensor* tensors, uint32_t n_tensors,
                         void* copy_stream, void* compaction_done);
 
+/* One host-to-device request of the pipelined schedule below. */
+typedef struct wm_piece {
+  uint32_t tensor;      /* index into the caller's tensor array                        */
+  uint32_t early;       /* 1: enqueued before the wait on the compaction event         */
+  uint64_t src_offset;  /* bytes from tensors[tensor].host_ptr                          */
+  uint64_t dst_offset;  /* bytes from the start of the reclaimed region                */
+  uint64_t bytes;
+} wm_piece;
+
+/* Block-granular pipelining of the weight stream (the paper pipelines page
+ * mapping and copying: "as soon as a page is mapped, its copy is issued",
+ * App. C).  A block of the reclaimed region that was free when the plan was
+ * made is ready at once; one that holds a moving block is ready only after
+ * kv_compact has read it.  live_host [host] is the bitmap kv_plan_reclaim was
+ * given (before the move).  Tensors are walked in the caller's order and cut
+ * at block boundaries; runs that lie wholly in free blocks become early pieces
+ * until early_bytes (0 = 128 MiB) have been collected; all other bytes become
+ * late pieces, one per tensor remainder run.  Host arithmetic only.
+ * Writes at most `capacity` pieces to out [host] (early pieces first) and the
+ * full count to *n_out; returns KV_E_TOOBIG if capacity is too small, and the
+ * validation errors of weights_materialize. */
+int weights_materialize_schedule(const kv_pool_desc* pool, uint32_t boundary,
+                                 const uint64_t* live_host,
+                                 const wm_tensor* tensors, uint32_t n_tensors,
+                                 uint64_t early_bytes, wm_piece* out,
+                                 uint32_t capacity, uint32_t* n_out);
+
+/* weights_materialize with that schedule: same bytes in the pool, but the
+ * early pieces are enqueued on copy_stream before the wait on compaction_done
+ * and so overlap the block copy; the late pieces follow the event. */
+int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
+                                  const uint64_t* live_host,
+                                  const wm_tensor* tensors, uint32_t n_tensors,
+                                  uint64_t early_bytes,
+                                  void* copy_stream, void* compaction_done);
+
 /* Reserved KV space of a draining instance, Sec. 3.3 Eq. 4, in blocks:
  * R = max(C*Q/B, T + C/B), fractional blocks rounded up, capped at C.
  * C = capacity_blocks (<= 2^32 - 1), T = used_blocks, Q = running requests,

@@ -30,7 +30,8 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
           KV_E_NOSPACE: "KV_E_NOSPACE", KV_E_BADPLAN: "KV_E_BADPLAN"}
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
-           "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "kv_reserve_blocks", "warmkv_version")
+           "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
+           "weights_materialize_pipelined", "kv_reserve_blocks", "warmkv_version")
 
 
 class WarmKVError(RuntimeError):
@@ -60,6 +61,11 @@ class kv_compact_tuning(Structure):
 
 class wm_tensor(Structure):
     _fields_ = [("host_ptr", c_void_p), ("bytes", c_uint64), ("dst_offset", c_uint64)]
+
+
+class wm_piece(Structure):
+    _fields_ = [("tensor", c_uint32), ("early", c_uint32), ("src_offset", c_uint64), ("dst_offset", c_uint64),
+                ("bytes", c_uint64)]
 
 
 _lib = None
@@ -93,6 +99,12 @@ def load():
     L.kv_plan_fetch.argtypes = [POINTER(kv_plan), c_void_p, POINTER(kv_plan_state)]
     L.weights_materialize.restype = c_int
     L.weights_materialize.argtypes = [POINTER(kv_pool_desc), c_uint32, POINTER(wm_tensor), c_uint32, c_void_p, c_void_p]
+    L.weights_materialize_schedule.restype = c_int
+    L.weights_materialize_schedule.argtypes = [POINTER(kv_pool_desc), c_uint32, c_void_p, POINTER(wm_tensor), c_uint32,
+                                               c_uint64, POINTER(wm_piece), c_uint32, POINTER(c_uint32)]
+    L.weights_materialize_pipelined.restype = c_int
+    L.weights_materialize_pipelined.argtypes = [POINTER(kv_pool_desc), c_uint32, c_void_p, POINTER(wm_tensor), c_uint32,
+                                                c_uint64, c_void_p, c_void_p]
     L.kv_reserve_blocks.restype = c_int64
     L.kv_reserve_blocks.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
     L.warmkv_version.restype = c_char_p
@@ -155,12 +167,44 @@ def kv_plan_fetch(plan: kv_plan, stream=0) -> kv_plan_state:
 
 def weights_materialize(pool: kv_pool_desc, boundary: int, tensors, copy_stream=0, compaction_done=None) -> None:
     """tensors: iterable of (host buffer or address, bytes, dst_offset)."""
+    arr, n = _tensor_array(tensors)
+    _check("weights_materialize", load().weights_materialize(byref(pool), boundary, arr, n,
+                                                              _ptr(copy_stream), _ptr(compaction_done)))
+
+
+def _tensor_array(tensors):
     items = list(tensors)
     arr = (wm_tensor * max(1, len(items)))()
     for i, (host, nbytes, off) in enumerate(items):
         arr[i] = wm_tensor(_ptr(host), nbytes, off)
-    _check("weights_materialize", load().weights_materialize(byref(pool), boundary, arr, len(items),
-                                                              _ptr(copy_stream), _ptr(compaction_done)))
+    return arr, len(items)
+
+
+def weights_materialize_schedule(pool: kv_pool_desc, boundary: int, live_host, tensors, early_bytes: int = 0):
+    """Returns the list of (tensor, early, src_offset, dst_offset, bytes).  live_host: host address or
+    a numpy uint64 array."""
+    arr, n = _tensor_array(tensors)
+    live_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
+    count = c_uint32(0)
+    cap = 64
+    while True:
+        out = (wm_piece * cap)()
+        rc = load().weights_materialize_schedule(byref(pool), boundary, live_ptr, arr, n, early_bytes, out, cap,
+                                                 byref(count))
+        if rc == KV_E_TOOBIG and count.value > cap:
+            cap = count.value
+            continue
+        _check("weights_materialize_schedule", rc)
+        return [(p.tensor, p.early, p.src_offset, p.dst_offset, p.bytes) for p in out[:count.value]]
+
+
+def weights_materialize_pipelined(pool: kv_pool_desc, boundary: int, live_host, tensors, early_bytes: int = 0,
+                                  copy_stream=0, compaction_done=None) -> None:
+    arr, n = _tensor_array(tensors)
+    live_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
+    _check("weights_materialize_pipelined",
+           load().weights_materialize_pipelined(byref(pool), boundary, live_ptr, arr, n, early_bytes,
+                                                _ptr(copy_stream), _ptr(compaction_done)))
 
 
 def kv_reserve_blocks(capacity_blocks: int, used_blocks: int, running: int, max_batch: int) -> int:

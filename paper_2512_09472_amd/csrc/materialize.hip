@@ -5,9 +5,10 @@
 // The copies go to the DMA engines through hipMemcpyAsync on a stream of
 // their own, so they take no CU away from the block copy they overlap with.
 // The reclaimed range still holds moving blocks until kv_compact has read
-// them; the copy stream therefore waits on the caller's compaction event
-// before the first chunk (the paper's rule "copy as soon as the destination is
-// ready", at the granularity of the whole region).
+// them.  The plain entry point therefore waits on the caller's compaction
+// event before the first request.  The pipelined one follows the paper's rule
+// "copy as soon as the destination is ready" at block granularity: bytes that
+// land in blocks that were free when the plan was made go out before the wait.
 #include <algorithm>
 #include <vector>
 
@@ -15,26 +16,29 @@
 
 namespace warmkv {
 namespace {
-constexpr uint64_t kChunkBytes = 256ull << 20;  // bound on one DMA request
-}
-}  // namespace warmkv
 
-using namespace warmkv;
+constexpr uint64_t kChunkBytes = 256ull << 20;   // bound on one DMA request
+constexpr uint64_t kDefaultEarly = 128ull << 20;  // early bytes when the caller passes 0: about what the link
+                                                 // carries during a few ms of block copy; every piece
+                                                 // costs ~10 us of request overhead, so more loses
 
-extern "C" int weights_materialize(const kv_pool_desc* pool, uint32_t boundary, const wm_tensor* tensors,
-                                   uint32_t n_tensors, void* copy_stream, void* compaction_done) {
+struct Region {
+  uint64_t block_bytes, offset, bytes;
+};
+
+// Every extent inside the region and pairwise disjoint, before any byte moves.
+int validate(const kv_pool_desc* pool, uint32_t boundary, const wm_tensor* tensors, uint32_t n_tensors,
+             Region* region) {
   if (pool == nullptr || (n_tensors != 0 && tensors == nullptr)) return KV_E_NULL;
   if (boundary > pool->num_blocks) return KV_E_RANGE;
-  const uint64_t block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
-  const uint64_t region_offset = (uint64_t)boundary * block_bytes;
-  const uint64_t region_bytes = (uint64_t)(pool->num_blocks - boundary) * block_bytes;
-
-  // Validate everything before the first byte moves.
+  region->block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
+  region->offset = (uint64_t)boundary * region->block_bytes;
+  region->bytes = (uint64_t)(pool->num_blocks - boundary) * region->block_bytes;
   std::vector<uint32_t> order;
   order.reserve(n_tensors);
   for (uint32_t i = 0; i < n_tensors; ++i) {
     const wm_tensor& t = tensors[i];
-    if (t.dst_offset > region_bytes || t.bytes > region_bytes - t.dst_offset) return KV_E_TOOBIG;
+    if (t.dst_offset > region->bytes || t.bytes > region->bytes - t.dst_offset) return KV_E_TOOBIG;
     if (t.bytes == 0) continue;
     if (t.host_ptr == nullptr) return KV_E_NULL;
     order.push_back(i);
@@ -46,21 +50,125 @@ extern "C" int weights_materialize(const kv_pool_desc* pool, uint32_t boundary, 
     const wm_tensor& prev = tensors[order[j - 1]];
     if (prev.dst_offset + prev.bytes > tensors[order[j]].dst_offset) return KV_E_OVERLAP;
   }
+  return KV_OK;
+}
 
-  hipStream_t s = (hipStream_t)copy_stream;
-  if (compaction_done != nullptr) {
-    const int rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+int enqueue(uint8_t* dst, const uint8_t* src, uint64_t bytes, hipStream_t s) {
+  for (uint64_t done = 0; done < bytes; done += kChunkBytes) {
+    const uint64_t len = std::min(kChunkBytes, bytes - done);
+    const int rc = hip_rc(hipMemcpyAsync(dst + done, src + done, len, hipMemcpyHostToDevice, s));
     if (rc != KV_OK) return rc;
   }
-  uint8_t* region = (uint8_t*)pool->base + region_offset;
-  for (uint32_t i = 0; i < n_tensors; ++i) {  // caller's order
+  return KV_OK;
+}
+
+inline bool was_live(const uint64_t* live, uint64_t block) { return (live[block >> 6] >> (block & 63)) & 1ull; }
+
+// Cut the tensors at block boundaries into early pieces (runs of blocks that
+// were free before the move, while the early budget lasts) and late pieces.
+void schedule(const Region& r, uint32_t boundary, const uint64_t* live, const wm_tensor* tensors,
+              uint32_t n_tensors, uint64_t early_budget, std::vector<wm_piece>* early,
+              std::vector<wm_piece>* late) {
+  uint64_t early_total = 0;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
     const wm_tensor& t = tensors[i];
-    for (uint64_t done = 0; done < t.bytes; done += kChunkBytes) {
-      const uint64_t len = std::min(kChunkBytes, t.bytes - done);
-      const int rc = hip_rc(hipMemcpyAsync(region + t.dst_offset + done, (const uint8_t*)t.host_ptr + done,
-                                           len, hipMemcpyHostToDevice, s));
-      if (rc != KV_OK) return rc;
+    uint64_t pos = 0;  // bytes of this tensor already assigned
+    while (pos < t.bytes) {
+      const uint64_t at = t.dst_offset + pos;
+      const uint64_t block = boundary + at / r.block_bytes;
+      const bool ready = early_total < early_budget && !was_live(live, block);
+      // extend over following blocks of the same kind
+      uint64_t end = std::min(t.bytes, pos + (r.block_bytes - at % r.block_bytes));
+      uint64_t collected = early_total + (ready ? end - pos : 0);
+      while (end < t.bytes) {
+        const uint64_t next_block = boundary + (t.dst_offset + end) / r.block_bytes;
+        const bool next_ready = collected < early_budget && !was_live(live, next_block);
+        if (next_ready != ready) break;
+        const uint64_t next_end = std::min(t.bytes, end + r.block_bytes);
+        if (ready) collected += next_end - end;
+        end = next_end;
+      }
+      wm_piece p;
+      p.tensor = i;
+      p.early = ready ? 1u : 0u;
+      p.src_offset = pos;
+      p.dst_offset = at;
+      p.bytes = end - pos;
+      (ready ? early : late)->push_back(p);
+      if (ready) early_total += p.bytes;
+      pos = end;
     }
+  }
+}
+
+}  // namespace
+}  // namespace warmkv
+
+using namespace warmkv;
+
+extern "C" int weights_materialize(const kv_pool_desc* pool, uint32_t boundary, const wm_tensor* tensors,
+                                   uint32_t n_tensors, void* copy_stream, void* compaction_done) {
+  Region r;
+  int rc = validate(pool, boundary, tensors, n_tensors, &r);
+  if (rc != KV_OK) return rc;
+  hipStream_t s = (hipStream_t)copy_stream;
+  if (compaction_done != nullptr) {
+    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+    if (rc != KV_OK) return rc;
+  }
+  uint8_t* region = (uint8_t*)pool->base + r.offset;
+  for (uint32_t i = 0; i < n_tensors; ++i) {  // caller's order
+    rc = enqueue(region + tensors[i].dst_offset, (const uint8_t*)tensors[i].host_ptr, tensors[i].bytes, s);
+    if (rc != KV_OK) return rc;
+  }
+  return KV_OK;
+}
+
+extern "C" int weights_materialize_schedule(const kv_pool_desc* pool, uint32_t boundary,
+                                            const uint64_t* live_host, const wm_tensor* tensors,
+                                            uint32_t n_tensors, uint64_t early_bytes, wm_piece* out,
+                                            uint32_t capacity, uint32_t* n_out) {
+  Region r;
+  const int rc = validate(pool, boundary, tensors, n_tensors, &r);
+  if (rc != KV_OK) return rc;
+  if (n_out == nullptr || (capacity != 0 && out == nullptr)) return KV_E_NULL;
+  if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
+  if (r.block_bytes == 0) return KV_E_RANGE;
+  std::vector<wm_piece> early, late;
+  schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
+  const size_t total = early.size() + late.size();
+  if (total > 0xFFFFFFFFull) return KV_E_RANGE;
+  *n_out = (uint32_t)total;
+  if (total > capacity) return KV_E_TOOBIG;
+  std::copy(early.begin(), early.end(), out);
+  std::copy(late.begin(), late.end(), out + early.size());
+  return KV_OK;
+}
+
+extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
+                                             const uint64_t* live_host, const wm_tensor* tensors,
+                                             uint32_t n_tensors, uint64_t early_bytes, void* copy_stream,
+                                             void* compaction_done) {
+  Region r;
+  int rc = validate(pool, boundary, tensors, n_tensors, &r);
+  if (rc != KV_OK) return rc;
+  if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
+  if (r.block_bytes == 0) return KV_E_RANGE;
+  std::vector<wm_piece> early, late;
+  schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
+  hipStream_t s = (hipStream_t)copy_stream;
+  uint8_t* region = (uint8_t*)pool->base + r.offset;
+  for (const wm_piece& p : early) {
+    rc = enqueue(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes, s);
+    if (rc != KV_OK) return rc;
+  }
+  if (compaction_done != nullptr) {
+    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+    if (rc != KV_OK) return rc;
+  }
+  for (const wm_piece& p : late) {
+    rc = enqueue(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes, s);
+    if (rc != KV_OK) return rc;
   }
   return KV_OK;
 }

@@ -36,6 +36,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.kv_plan) == 56
     assert ctypes.sizeof(binding.kv_compact_tuning) == 16
     assert ctypes.sizeof(binding.wm_tensor) == 24
+    assert ctypes.sizeof(binding.wm_piece) == 32
 
 
 def test_workspace_and_bind():
@@ -107,6 +108,52 @@ def test_materialize_validates_every_extent_first():
     assert code([(FAKE, 32, 0)], boundary=nb + 1) == wk.KV_E_RANGE
     wk.weights_materialize(pool, b, [])                       # nothing to copy
     wk.weights_materialize(pool, b, [(0, 0, 5), (0, 0, 5)])   # empty extents never overlap
+
+
+def test_materialize_schedule_partitions_tensors_and_respects_readiness():
+    """Early pieces touch only blocks that were free before the move; together with the late
+    pieces they cover every tensor byte exactly once, in order."""
+    import numpy as np
+    from synth import bitmap_from_ids
+    nb, b, layers, tile = 96, 40, 2, 512
+    bb = layers * tile
+    rs = np.random.default_rng(2)
+    live_bits = rs.random(nb) < 0.5
+    live = bitmap_from_ids(np.flatnonzero(live_bits), nb)
+    pool = wk.pool_desc(FAKE, nb, layers, tile)
+    region = (nb - b) * bb
+    tensors = [(FAKE, 3000, 0), (FAKE, 5 * bb + 17, 3000), (FAKE, 0, 9000), (FAKE, bb, 20 * bb),
+               (FAKE, 7, 30 * bb + 5), (FAKE, 10 * bb - 100, region - 10 * bb + 100)]
+    for budget in (1, 2 * bb, 6 * bb + 1, 0):
+        pieces = wk.weights_materialize_schedule(pool, b, live, tensors, early_bytes=budget)
+        flags = [e for _, e, _, _, _ in pieces]
+        assert flags == sorted(flags, reverse=True), "early pieces come first"
+        early_total = 0
+        for i, (_, nbytes, off) in enumerate(tensors):
+            mine = sorted((p for p in pieces if p[0] == i), key=lambda p: p[2])
+            pos = 0
+            for _, early, so, do, n in mine:
+                assert so == pos and do == off + so and n > 0
+                pos += n
+                blocks = range(b + do // bb, b + (do + n - 1) // bb + 1)
+                if early:
+                    assert not any(live_bits[j] for j in blocks)
+                    early_total += n
+            assert pos == nbytes
+        limit = budget if budget else 128 << 20
+        assert early_total < limit + bb
+        if budget == 1:
+            assert sum(flags) == 1
+    # with nothing live above the boundary everything up to the budget is early
+    none_live = bitmap_from_ids(np.flatnonzero(live_bits[:b]), nb)
+    pieces = wk.weights_materialize_schedule(pool, b, none_live, tensors, early_bytes=1 << 40)
+    assert all(e == 1 for _, e, _, _, _ in pieces) and len(pieces) == 5
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.weights_materialize_schedule(pool, b, 0, tensors)
+    assert e.value.code == wk.KV_E_NULL
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.weights_materialize_pipelined(pool, b, live, [(FAKE, 16, 0), (FAKE, 16, 8)])
+    assert e.value.code == wk.KV_E_OVERLAP
 
 
 def test_reserve_blocks_matches_eq4_fixtures():

@@ -282,3 +282,43 @@ def test_materialize_matches_oracle_and_overlaps_compaction(oracle):
                            s_copy.cuda_stream, done.cuda_event)
     torch.cuda.synchronize()
     assert np.array_equal(pool_dev.cpu().numpy(), want)
+
+
+def test_pipelined_materialize_matches_oracle(oracle):
+    """Block-granular pipelining: early pieces go out before the compaction event, the rest
+    after it; the pool must hold exactly what the oracle's plain copy produces."""
+    cfg = CONFIGS[2].scaled(num_blocks=768, num_layers=2, num_seqs=64)
+    w = make_workload(cfg)
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    bb = cfg.block_bytes
+    region_bytes = (cfg.num_blocks - cfg.boundary) * bb
+    wtable = content.normal_bf16_table(0.02)
+    sizes = [5 * bb + 4096, 256, 17 * bb, 3 * bb - 512, region_bytes // 4]
+    offs = [0, 5 * bb + 4096, 6 * bb, 24 * bb + 512, region_bytes - region_bytes // 4]
+    hosts = []
+    for i, sz in enumerate(sizes):
+        h = torch.empty(sz, dtype=torch.uint8, pin_memory=True)
+        h.numpy()[:] = content.item_bytes_host(0xFEED, i, -(-sz // 8) * 8, wtable)[:sz]
+        hosts.append(h)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want = pool0.copy()
+    oracle.compact(want, bb, p)
+    assert oracle.materialize(want, cfg.boundary * bb, [(h.numpy(), o) for h, o in zip(hosts, offs)]) == 0
+    tensors = [(h, h.numel(), o) for h, o in zip(hosts, offs)]
+    for early_bytes in (0, 3 * bb, 1):
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+        pieces = wk.weights_materialize_schedule(pool, cfg.boundary, w.live, tensors, early_bytes)
+        assert any(e for _, e, *_ in pieces) and (early_bytes == 0 or any(not e for _, e, *_ in pieces))
+        dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+        live_dev = gh.to_dev(w.live)
+        s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+        done = torch.cuda.Event()
+        torch.cuda.synchronize()
+        wk.kv_plan_reclaim(live_dev, dp.plan, s_compute.cuda_stream)
+        wk.kv_compact(pool, dp.plan, s_compute.cuda_stream)
+        done.record(s_compute)
+        wk.weights_materialize_pipelined(pool, cfg.boundary, w.live, tensors, early_bytes,
+                                         s_copy.cuda_stream, done.cuda_event)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want), f"early_bytes={early_bytes}"

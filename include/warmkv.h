@@ -216,6 +216,22 @@ int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
 int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks,
                           uint32_t running, uint32_t max_batch);
 
+/* Reverse switch: the reserve proved too small, so prewarmed weights give
+ * space back ("when the reserved KV cache space becomes insufficient to serve
+ * existing requests, we evict prewarmed weights", Sec. 3.3).  The boundary
+ * rises from old_boundary to new_boundary (old <= new <= num_blocks); blocks
+ * [old, new) return to the KV allocator as free ids (no block is live there,
+ * so no bitmap bit changes and no byte moves).  For every tensor placed by
+ * weights_materialize relative to the old region: evicted[i] = 1 if it has a
+ * byte inside the returned blocks (it is lost), else 0 and new_offset[i] is its
+ * offset relative to the new region's start.  Host arithmetic only; evicted,
+ * new_offset [host] have n_tensors entries.  Returns the number of evicted
+ * tensors, or KV_E_RANGE / KV_E_NULL / KV_E_TOOBIG (an extent outside the
+ * old region). */
+int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint32_t new_boundary,
+                const wm_tensor* tensors, uint32_t n_tensors,
+                uint8_t* evicted, uint64_t* new_offset);
+
 /* Library version, "major.minor". */
 const char* warmkv_version(void);
 

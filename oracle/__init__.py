@@ -60,6 +60,8 @@ def lib():
         L.oracle_remap.argtypes = [vp, u64, vp, u32]
         L.oracle_materialize.restype = ctypes.c_int
         L.oracle_materialize.argtypes = [vp, u64, u64, ctypes.POINTER(_Tensor), u32]
+        L.oracle_grow.restype = ctypes.c_int64
+        L.oracle_grow.argtypes = [u64, u32, u32, u32, ctypes.POINTER(_Tensor), u32, vp, vp]
         L.oracle_reserve_blocks.restype = ctypes.c_int64
         L.oracle_reserve_blocks.argtypes = [u64, u64, u32, u32]
         _lib = L
@@ -142,3 +144,18 @@ def materialize(pool: np.ndarray, region_offset: int, tensors) -> int:
 
 def reserve_blocks(capacity_blocks: int, used_blocks: int, running: int, max_batch: int) -> int:
     return int(lib().oracle_reserve_blocks(capacity_blocks, used_blocks, running, max_batch))
+
+
+def grow(block_bytes: int, num_blocks: int, old_boundary: int, new_boundary: int, extents):
+    """extents: iterable of (bytes, dst_offset).  Returns (n_lost, evicted uint8[], new_offset uint64[])
+    or (negative error, None, None)."""
+    extents = list(extents)
+    arr = (_Tensor * max(1, len(extents)))()
+    for i, (nbytes, off) in enumerate(extents):
+        arr[i] = _Tensor(None, nbytes, off)
+    ev = np.zeros(max(1, len(extents)), dtype=np.uint8)
+    no = np.zeros(max(1, len(extents)), dtype=np.uint64)
+    rc = int(lib().oracle_grow(block_bytes, num_blocks, old_boundary, new_boundary, arr, len(extents), _p(ev), _p(no)))
+    if rc < 0:
+        return rc, None, None
+    return rc, ev[:len(extents)], no[:len(extents)]

@@ -157,4 +157,33 @@ int64_t oracle_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks, ui
   return (int64_t)R;
 }
 
+// Reverse switch (Sec. 3.3: weights are evicted when the reserve runs short).
+// The boundary rises from old_boundary to new_boundary; a tensor is lost if any
+// of its bytes lies in a block that goes back to the KV cache.  Checked byte
+// range by byte range: the tensor occupies absolute pool bytes [lo, hi), the
+// returned blocks occupy [old_boundary, new_boundary) * block_bytes.
+// Returns the number of lost tensors or a negative error.
+int64_t oracle_grow(uint64_t block_bytes, uint32_t num_blocks, uint32_t old_boundary,
+                    uint32_t new_boundary, const oracle_tensor* tensors, uint32_t n_tensors,
+                    uint8_t* evicted, uint64_t* new_offset) {
+  if (n_tensors && (!tensors || !evicted || !new_offset)) return ORACLE_E_NULL;
+  if (old_boundary > new_boundary || new_boundary > num_blocks) return ORACLE_E_RANGE;
+  const uint64_t pool_bytes = (uint64_t)num_blocks * block_bytes;
+  const uint64_t given_back_lo = (uint64_t)old_boundary * block_bytes;
+  const uint64_t given_back_hi = (uint64_t)new_boundary * block_bytes;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const uint64_t lo = given_back_lo + tensors[i].dst_offset;
+    if (lo > pool_bytes || tensors[i].bytes > pool_bytes - lo) return ORACLE_E_TOOBIG;
+  }
+  int64_t lost = 0;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const uint64_t lo = given_back_lo + tensors[i].dst_offset, hi = lo + tensors[i].bytes;
+    const bool overlaps = lo < hi && lo < given_back_hi && given_back_lo < hi;
+    evicted[i] = overlaps;
+    new_offset[i] = (!overlaps && lo >= given_back_hi) ? lo - given_back_hi : 0;
+    lost += overlaps;
+  }
+  return lost;
+}
+
 }  // extern "C"

@@ -31,7 +31,7 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
-           "weights_materialize_pipelined", "kv_reserve_blocks", "warmkv_version")
+           "weights_materialize_pipelined", "kv_reserve_blocks", "kv_grow", "warmkv_version")
 
 
 class WarmKVError(RuntimeError):
@@ -107,6 +107,8 @@ def load():
                                                 c_uint64, c_void_p, c_void_p]
     L.kv_reserve_blocks.restype = c_int64
     L.kv_reserve_blocks.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
+    L.kv_grow.restype = c_int64
+    L.kv_grow.argtypes = [POINTER(kv_pool_desc), c_uint32, c_uint32, POINTER(wm_tensor), c_uint32, c_void_p, c_void_p]
     L.warmkv_version.restype = c_char_p
     L.warmkv_version.argtypes = []
     _lib = L
@@ -212,6 +214,18 @@ def kv_reserve_blocks(capacity_blocks: int, used_blocks: int, running: int, max_
     if r < 0:
         raise WarmKVError("kv_reserve_blocks", r)
     return r
+
+
+def kv_grow(pool: kv_pool_desc, old_boundary: int, new_boundary: int, tensors):
+    """tensors: iterable of (host buffer or address, bytes, dst_offset) as given to weights_materialize.
+    Returns (n_evicted, evicted flags, new offsets) as Python lists."""
+    arr, n = _tensor_array(tensors)
+    ev = (ctypes.c_uint8 * max(1, n))()
+    no = (c_uint64 * max(1, n))()
+    r = int(load().kv_grow(byref(pool), old_boundary, new_boundary, arr, n, ev, no))
+    if r < 0:
+        raise WarmKVError("kv_grow", r)
+    return r, list(ev[:n]), list(no[:n])
 
 
 def warmkv_version() -> str:

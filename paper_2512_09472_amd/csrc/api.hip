@@ -72,4 +72,27 @@ extern "C" int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blo
   return (int64_t)(r > capacity_blocks ? capacity_blocks : r);
 }
 
+// Sec. 3.3, last sentence: weights are evicted when the reserve runs short.
+extern "C" int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint32_t new_boundary,
+                           const wm_tensor* tensors, uint32_t n_tensors, uint8_t* evicted,
+                           uint64_t* new_offset) {
+  if (pool == nullptr) return KV_E_NULL;
+  if (n_tensors != 0 && (tensors == nullptr || evicted == nullptr || new_offset == nullptr)) return KV_E_NULL;
+  if (old_boundary > new_boundary || new_boundary > pool->num_blocks) return KV_E_RANGE;
+  const uint64_t block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
+  const uint64_t old_region = (uint64_t)(pool->num_blocks - old_boundary) * block_bytes;
+  const uint64_t returned = (uint64_t)(new_boundary - old_boundary) * block_bytes;
+  for (uint32_t i = 0; i < n_tensors; ++i)
+    if (tensors[i].dst_offset > old_region || tensors[i].bytes > old_region - tensors[i].dst_offset)
+      return KV_E_TOOBIG;
+  int64_t lost = 0;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const bool hit = tensors[i].bytes != 0 && tensors[i].dst_offset < returned;
+    evicted[i] = hit ? 1 : 0;
+    new_offset[i] = hit ? 0 : (tensors[i].dst_offset >= returned ? tensors[i].dst_offset - returned : 0);
+    lost += hit;
+  }
+  return lost;
+}
+
 extern "C" const char* warmkv_version(void) { return "0.1"; }

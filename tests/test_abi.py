@@ -175,3 +175,43 @@ def test_reserve_blocks_matches_oracle(oracle):
         B = rng.randint(1, 512)
         Q = rng.randint(0, B + 3)
         assert wk.kv_reserve_blocks(C, T, Q, B) == oracle.reserve_blocks(C, T, Q, B)
+
+
+def test_grow_matches_oracle_and_hand_cases(oracle):
+    """Reverse switch: which tensors are lost when blocks [old, new) go back to the KV cache."""
+    import numpy as np
+    nb, layers, tile = 100, 2, 512
+    bb = layers * tile
+    pool = wk.pool_desc(FAKE, nb, layers, tile)
+    # hand cases, old boundary 60 (region 40 blocks), 5 blocks returned
+    ext = [(bb, 0), (bb, 4 * bb), (1, 5 * bb - 1), (1, 5 * bb), (3 * bb, 10 * bb), (0, 2 * bb), (bb, 39 * bb)]
+    n, ev, no = wk.kv_grow(pool, 60, 65, [(FAKE, b, o) for b, o in ext])
+    assert (n, ev) == (3, [1, 1, 1, 0, 0, 0, 0])
+    assert no[3:] == [0, 5 * bb, 0, 34 * bb]
+    assert wk.kv_grow(pool, 60, 60, [(FAKE, b, o) for b, o in ext])[0] == 0
+    assert wk.kv_grow(pool, 60, 100, [(FAKE, b, o) for b, o in ext])[0] == 6
+    for args, code in (((60, 59), wk.KV_E_RANGE), ((60, 101), wk.KV_E_RANGE)):
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.kv_grow(pool, *args, [(FAKE, 1, 0)])
+        assert e.value.code == code
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.kv_grow(pool, 60, 70, [(FAKE, 2, 40 * bb - 1)])
+    assert e.value.code == wk.KV_E_TOOBIG
+    # random cases against the oracle and against a per-byte brute force
+    rs = np.random.default_rng(12)
+    for _ in range(300):
+        old = int(rs.integers(0, nb + 1))
+        new = int(rs.integers(old, nb + 1))
+        region = (nb - old) * bb
+        ext = []
+        for _ in range(int(rs.integers(0, 8))):
+            off = int(rs.integers(0, region + 1))
+            ext.append((int(rs.integers(0, region - off + 1)), off))
+        n, ev, no = wk.kv_grow(pool, old, new, [(FAKE, b, o) for b, o in ext])
+        on, oev, ono = oracle.grow(bb, nb, old, new, ext)
+        assert n == on and ev == oev.tolist()
+        for i, (b, o) in enumerate(ext):
+            first_byte_returned = old * bb + o < new * bb     # extents only extend upwards from o
+            assert bool(ev[i]) == (b > 0 and first_byte_returned)
+            if not ev[i] and b > 0:
+                assert no[i] == ono[i] == old * bb + o - new * bb

@@ -256,6 +256,35 @@ def test_materialize_rejects_before_writing(oracle):
     assert oracle.materialize(pool, b * bb, [(ok, 0), (ok, 16), (ok, 112)]) == 0
 
 
+def test_grow_hand_cases_and_byte_brute_force(oracle):
+    """Reverse switch: a tensor is lost iff one of its bytes lies in a returned block."""
+    bb, nb = 64, 30
+    # old boundary 10, 3 blocks returned: pool bytes [640, 832) go back to the KV cache
+    ext = [(64, 0), (1, 191), (1, 192), (200, 100), (0, 50), (10, 1270)]
+    n, ev, no = oracle.grow(bb, nb, 10, 13, ext)
+    assert n == 3 and ev.tolist() == [1, 1, 0, 1, 0, 0]
+    assert no.tolist()[2] == 0 and no.tolist()[5] == 1270 - 192
+    assert oracle.grow(bb, nb, 10, 13, [(11, 1270)])[0] == oracle.E_TOOBIG
+    assert oracle.grow(bb, nb, 13, 10, [])[0] == oracle.E_RANGE
+    rs = np.random.default_rng(4)
+    for _ in range(200):
+        old = int(rs.integers(0, nb + 1))
+        new = int(rs.integers(old, nb + 1))
+        region = (nb - old) * bb
+        ext = []
+        for _ in range(5):
+            off = int(rs.integers(0, region + 1))
+            ext.append((int(rs.integers(0, region - off + 1)), off))
+        n, ev, no = oracle.grow(bb, nb, old, new, ext)
+        owner = np.zeros(nb * bb, dtype=bool)
+        owner[old * bb:new * bb] = True                      # bytes that go back
+        for i, (b, o) in enumerate(ext):
+            assert bool(ev[i]) == bool(owner[old * bb + o: old * bb + o + b].any())
+            if b and not ev[i]:
+                assert old * bb + o == new * bb + int(no[i])  # same absolute place, new origin
+        assert n == int(ev.sum())
+
+
 # ----------------------------------------------------------------- mutants
 class _Mut:
     def __init__(self, p, **kw):

@@ -53,6 +53,10 @@ def parse_args():
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(a known-size reference for profiler byte counters)")
+    ap.add_argument("--vmm-compare", type=int, default=0, metavar="BLOCKS",
+                    help="also time the no-move variant (HIP virtual-memory remapping of unused blocks' pages) on a "
+                         "pool of this many blocks of the config's shape; 20480 = the full 8B-shaped pool, which "
+                         "takes about half a minute, most of it tearing the pool down")
     return ap.parse_args()
 
 
@@ -271,6 +275,26 @@ def main():
                               "overlapped_ms": round(t_overlap, 2),
                               "block_pipelined_ms": round(t_pipe, 2)}
         del host
+
+    if args.vmm_compare:
+        del pool_t
+        torch.cuda.empty_cache()
+        vcfg = cfg.scaled(num_blocks=args.vmm_compare)
+        vw = make_workload(vcfg)
+        want = vcfg.num_blocks - vcfg.boundary
+        t0 = time.perf_counter()
+        vp = wk.kv_vmm_pool_create(vcfg.num_blocks, vcfg.block_bytes)
+        t1 = time.perf_counter()
+        wk.kv_vmm_reclaim(vp, vw.live, want)
+        t2 = time.perf_counter()
+        wk.kv_vmm_restore(vp)
+        t3 = time.perf_counter()
+        wk.kv_vmm_pool_destroy(vp)
+        out["vmm_compare"] = {"workload": f"{vcfg.num_blocks} blocks of {vcfg.block_bytes} B, pages of the {want} highest "
+                                          f"free blocks ({want * vcfg.block_bytes / 2**30:.2f} GiB) remapped into the slot",
+                              "create_ms": round((t1 - t0) * 1e3, 1), "reclaim_ms": round((t2 - t1) * 1e3, 1),
+                              "reclaim_us_per_block": round((t2 - t1) * 1e6 / want, 1),
+                              "restore_ms": round((t3 - t2) * 1e3, 1)}
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, w, sample_moves=2048)

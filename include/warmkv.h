@@ -232,6 +232,43 @@ int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint32_t new_bo
                 const wm_tensor* tensors, uint32_t n_tensors,
                 uint8_t* evicted, uint64_t* new_offset);
 
+/* ------------------------------------------------------------------------
+ * No-move variant: the paper's own mechanism on HIP's virtual-memory API
+ * (Sec. 3.4 and App. C: physical pages are pre-allocated once, a "prewarm
+ * slot" is a second virtual range, and the pages under unused KV blocks are
+ * mapped into it; nothing is copied and no block table changes).  Kept for
+ * comparison with compaction.  Unlike the rest of this library these calls
+ * own memory (physical handles and address ranges) and synchronise the device.
+ * ------------------------------------------------------------------------ */
+typedef struct kv_vmm_pool kv_vmm_pool;   /* opaque, host object */
+
+/* Create a pool of num_blocks physical allocations of block_bytes each
+ * (block_bytes must be a multiple of the device's allocation granularity:
+ * else KV_E_ALIGN), all mapped read-write into one contiguous KV range, and
+ * reserve an equally large, still unmapped slot range.  Current device. */
+int kv_vmm_pool_create(uint32_t num_blocks, uint64_t block_bytes, kv_vmm_pool** out);
+
+/* [device] base of the KV range (block i at + i*block_bytes while it is mapped
+ * there) and of the slot range. */
+void* kv_vmm_kv_base(const kv_vmm_pool* pool);
+void* kv_vmm_slot_base(const kv_vmm_pool* pool);
+
+/* Hand the pages of `want` unused blocks to the slot: the highest free ids of
+ * live_host [host bitmap, as for kv_plan_reclaim] are unmapped from the KV
+ * range and mapped, in descending id order, at slot offsets 0, block_bytes,
+ * ...; the slot prefix [0, want*block_bytes) is then readable and writable.
+ * Those ids must not be touched through the KV range until kv_vmm_restore.
+ * Fails with KV_E_NOSPACE (nothing changed) if fewer than `want` blocks are
+ * free, KV_E_RANGE if pages are already lent.  ids_out [host, may be NULL]
+ * receives the `want` ids.  Synchronises the device first. */
+int kv_vmm_reclaim(kv_vmm_pool* pool, const uint64_t* live_host, uint32_t want, int32_t* ids_out);
+
+/* Give every lent page back to its block's place in the KV range. */
+int kv_vmm_restore(kv_vmm_pool* pool);
+
+/* Unmap everything, release the physical memory and both ranges. */
+int kv_vmm_pool_destroy(kv_vmm_pool* pool);
+
 /* Library version, "major.minor". */
 const char* warmkv_version(void);
 

@@ -31,7 +31,8 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
-           "weights_materialize_pipelined", "kv_reserve_blocks", "kv_grow", "warmkv_version")
+           "weights_materialize_pipelined", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
+           "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "warmkv_version")
 
 
 class WarmKVError(RuntimeError):
@@ -109,6 +110,18 @@ def load():
     L.kv_reserve_blocks.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
     L.kv_grow.restype = c_int64
     L.kv_grow.argtypes = [POINTER(kv_pool_desc), c_uint32, c_uint32, POINTER(wm_tensor), c_uint32, c_void_p, c_void_p]
+    L.kv_vmm_pool_create.restype = c_int
+    L.kv_vmm_pool_create.argtypes = [c_uint32, c_uint64, POINTER(c_void_p)]
+    L.kv_vmm_kv_base.restype = c_void_p
+    L.kv_vmm_kv_base.argtypes = [c_void_p]
+    L.kv_vmm_slot_base.restype = c_void_p
+    L.kv_vmm_slot_base.argtypes = [c_void_p]
+    L.kv_vmm_reclaim.restype = c_int
+    L.kv_vmm_reclaim.argtypes = [c_void_p, c_void_p, c_uint32, c_void_p]
+    L.kv_vmm_restore.restype = c_int
+    L.kv_vmm_restore.argtypes = [c_void_p]
+    L.kv_vmm_pool_destroy.restype = c_int
+    L.kv_vmm_pool_destroy.argtypes = [c_void_p]
     L.warmkv_version.restype = c_char_p
     L.warmkv_version.argtypes = []
     _lib = L
@@ -226,6 +239,37 @@ def kv_grow(pool: kv_pool_desc, old_boundary: int, new_boundary: int, tensors):
     if r < 0:
         raise WarmKVError("kv_grow", r)
     return r, list(ev[:n]), list(no[:n])
+
+
+def kv_vmm_pool_create(num_blocks: int, block_bytes: int) -> int:
+    """Returns the opaque pool handle (an address)."""
+    out = c_void_p()
+    _check("kv_vmm_pool_create", load().kv_vmm_pool_create(num_blocks, block_bytes, byref(out)))
+    return out.value
+
+
+def kv_vmm_kv_base(pool: int) -> int:
+    return load().kv_vmm_kv_base(pool)
+
+
+def kv_vmm_slot_base(pool: int) -> int:
+    return load().kv_vmm_slot_base(pool)
+
+
+def kv_vmm_reclaim(pool: int, live_host, want: int) -> list[int]:
+    """live_host: numpy uint64 bitmap (host).  Returns the ids whose pages now back the slot, in slot order."""
+    ids = (c_int32 * max(1, want))()
+    live_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
+    _check("kv_vmm_reclaim", load().kv_vmm_reclaim(pool, live_ptr, want, ids))
+    return list(ids[:want])
+
+
+def kv_vmm_restore(pool: int) -> None:
+    _check("kv_vmm_restore", load().kv_vmm_restore(pool))
+
+
+def kv_vmm_pool_destroy(pool: int) -> None:
+    _check("kv_vmm_pool_destroy", load().kv_vmm_pool_destroy(pool))
 
 
 def warmkv_version() -> str:

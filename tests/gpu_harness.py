@@ -82,3 +82,13 @@ def run_reclaim(cfg, live: np.ndarray, tables: np.ndarray, pool_dev: torch.Tenso
     torch.cuda.synchronize()
     dp.live_dev = live_dev
     return dp, tables_dev
+
+
+class _RawDeviceBuffer:
+    def __init__(self, ptr: int, nbytes: int):
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False), "version": 2}
+
+
+def view_device(ptr: int, nbytes: int) -> torch.Tensor:
+    """uint8 tensor over device memory the caller owns (no copy, no ownership)."""
+    return torch.as_tensor(_RawDeviceBuffer(ptr, nbytes), device=dev())

@@ -322,3 +322,67 @@ def test_pipelined_materialize_matches_oracle(oracle):
                                          s_copy.cuda_stream, done.cuda_event)
         torch.cuda.synchronize()
         assert np.array_equal(pool_dev.cpu().numpy(), want), f"early_bytes={early_bytes}"
+
+
+def test_vmm_variant_lends_pages_without_moving_bytes():
+    """The no-move variant: pages of unused blocks appear back to back in the slot range,
+    live KV is untouched, weights written through the slot land in those pages, and a
+    restore puts every page back under its block."""
+    nb, bb, seed = 160, 2 << 20, 77
+    try:
+        pool = wk.kv_vmm_pool_create(nb, bb)
+    except wk.WarmKVError as e:
+        if e.code == wk.KV_E_ALIGN:
+            pytest.skip("allocation granularity does not divide 2 MiB")
+        raise
+    try:
+        kv_ptr, slot_ptr = wk.kv_vmm_kv_base(pool), wk.kv_vmm_slot_base(pool)
+        content.fill_device(kv_ptr, nb, bb, seed)
+        torch.cuda.synchronize()
+        rs = np.random.default_rng(3)
+        live_bits = rs.random(nb) < 0.55
+        live = bitmap_from_ids(np.flatnonzero(live_bits), nb)
+        free_desc = np.flatnonzero(~live_bits)[::-1]
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.kv_vmm_reclaim(pool, live, free_desc.size + 1)
+        assert e.value.code == wk.KV_E_NOSPACE
+        want = 40
+        ids = wk.kv_vmm_reclaim(pool, live, want)
+        assert ids == free_desc[:want].tolist()
+        kv = gh.view_device(kv_ptr, nb * bb)
+        slot = gh.view_device(slot_ptr, want * bb)
+        expect = torch.empty(bb, dtype=torch.uint8, device=gh.dev())
+
+        def check_block(t, index, cid):
+            content.fill_device(expect.data_ptr(), 1, bb, seed, cid0=cid)
+            assert torch.equal(t[index * bb:(index + 1) * bb], expect), (index, cid)
+
+        for k, i in enumerate(ids):                      # pages kept their bytes and their order
+            check_block(slot, k, i)
+        lent = set(ids)
+        for i in range(nb):                              # everything still mapped in the KV range is intact
+            if i not in lent:
+                check_block(kv, i, i)
+        weights = torch.empty(want * bb - 4096, dtype=torch.uint8, pin_memory=True)
+        weights.numpy()[:] = content.item_bytes_host(5, 1, weights.numel(), None)
+        slot[:weights.numel()].copy_(weights, non_blocking=True)
+        torch.cuda.synchronize()
+        assert torch.equal(slot[:weights.numel()].cpu(), weights)
+        for i in np.flatnonzero(live_bits).tolist():
+            check_block(kv, i, i)
+        with pytest.raises(wk.WarmKVError) as e:         # pages already lent
+            wk.kv_vmm_reclaim(pool, live, 1)
+        assert e.value.code == wk.KV_E_RANGE
+        del slot
+        wk.kv_vmm_restore(pool)
+        for i in np.flatnonzero(live_bits).tolist():
+            check_block(kv, i, i)
+        k = 3                                            # a returned page still holds the weight bytes written to it
+        assert torch.equal(kv[ids[k] * bb:(ids[k] + 1) * bb].cpu(), weights[k * bb:(k + 1) * bb])
+        ids2 = wk.kv_vmm_reclaim(pool, live, 5)          # and the pool can lend again
+        assert ids2 == ids[:5]
+        wk.kv_vmm_restore(pool)
+        del kv
+    finally:
+        torch.cuda.synchronize()
+        wk.kv_vmm_pool_destroy(pool)

@@ -53,6 +53,8 @@ def parse_args():
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(a known-size reference for profiler byte counters)")
+    ap.add_argument("--layout", choices=("block", "layer"), default="block",
+                    help="pool layout: block-major (default) or layer-major (one slab per layer)")
     ap.add_argument("--vmm-compare", type=int, default=0, metavar="BLOCKS",
                     help="also time the no-move variant (HIP virtual-memory remapping of unused blocks' pages) on a "
                          "pool of this many blocks of the config's shape; 20480 = the full 8B-shaped pool, which "
@@ -124,7 +126,8 @@ def main():
     ws_bytes = wk.kv_plan_workspace_bytes(cfg.num_blocks, cfg.boundary)
     ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
     plan = wk.kv_plan_bind(ws, ws_bytes, cfg.num_blocks, cfg.boundary)
-    pool = wk.pool_desc(pool_t, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    layer_stride = cfg.num_blocks * cfg.tile_bytes if args.layout == "layer" else 0
+    pool = wk.pool_desc(pool_t, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, layer_stride)
     stream = torch.cuda.Stream()
     s = stream.cuda_stream
     tuning = dict(workgroups=args.workgroups, chunk_bytes=args.chunk_bytes, flags=args.flags)
@@ -191,18 +194,19 @@ def main():
                    "reclaimed_GiB": round(reclaimed_bytes / 2**30, 3),
                    "ms_to_reclaim": round(ms_per_step, 4),
                    "pct_of_hbm_peak_whole_step": round(100 * rw_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
-                   "tuning": tuning},
+                   "layout": args.layout + "-major", "tuning": tuning},
         "roofline": {"bound": "hbm", "kernel": "compact_ticket_kernel",
                      "achieved": round(rw_bytes / (compact_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(rw_bytes / (compact_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
-                     "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.index, n_moves)) if not any(tuning.values()) else None,
+                     "traffic": (MEASURED_TRAFFIC_BYTES.get((cfg.index, n_moves))
+                                 if not any(tuning.values()) and args.layout == "block" else None),
                      "kernel_ms_avg": round(compact_avg, 4), "kernel_ms_min": round(min(compact_ms), 4),
                      "kernel_ms_median": round(statistics.median(compact_ms), 4),
                      "algorithmic_bytes_per_launch": rw_bytes},
     }
 
     # ---- weight materialisation leg (third configuration: same pool plus weights)
-    if not args.no_materialize and cfg.index in (1, 2):
+    if not args.no_materialize and cfg.index in (1, 2) and args.layout == "block":
         shapes = weight_shapes_8b()
         sizes = [2 * a * b for _, (a, b) in shapes]
         offs = dense_offsets(sizes)

@@ -30,10 +30,11 @@
  *     kv_compact and kv_remap_tables read it and do nothing unless it is KV_OK,
  *     so an infeasible request modifies no pool byte and no table entry
  *     (existing requests take precedence over prewarmed weights, Sec. 3.3).
- *   - Pool layout: one allocation, block-major.  Block i occupies bytes
- *     [i*block_bytes, (i+1)*block_bytes), block_bytes = num_layers*tile_bytes;
- *     within a block, layer l's K and V tile is tile_bytes bytes at l*tile_bytes.
- *     Bytes are never interpreted (bf16 or fp8 alike).
+ *   - Pool layout: one allocation, block-major by default: block i occupies
+ *     bytes [i*block_bytes, (i+1)*block_bytes), block_bytes = num_layers *
+ *     tile_bytes, layer l's K and V tile at + l*tile_bytes.  A layer-major pool
+ *     is described by kv_pool_desc.layer_stride_bytes.  Bytes are never
+ *     interpreted (bf16 or fp8 alike).
  *   - Re-entrant; no global state.  Two calls that touch the same plan or pool
  *     must be ordered by the caller (same stream, or events).
  */
@@ -57,12 +58,21 @@ extern "C" {
 #define KV_E_NOSPACE  (-7)  /* device status: more movers than free ids below the boundary   */
 #define KV_E_BADPLAN  (-8)  /* device status: a move violates src >= boundary > dst          */
 
-/* Describes the caller-owned paged KV pool. */
+/* Describes the caller-owned paged KV pool (one allocation).
+ * layer_stride_bytes == 0: block-major.  Block i is block_bytes = L*tile_bytes
+ *   contiguous bytes at i*block_bytes; layer l's tile sits at + l*tile_bytes.
+ * layer_stride_bytes != 0: layer-major (one slab per layer, the layout paged
+ *   attention engines usually keep).  Layer l's tile of block i sits at
+ *   l*layer_stride_bytes + i*tile_bytes; layer_stride_bytes >= NB*tile_bytes
+ *   and a multiple of 256.  A block is then L separate tiles and the reclaimed
+ *   space is L strips, one per slab: bytes [b*tile_bytes, NB*tile_bytes) of
+ *   each. */
 typedef struct kv_pool_desc {
-  void*    base;        /* [device] 256-byte aligned                                   */
-  uint32_t num_blocks;  /* NB, at most 2^24                                            */
-  uint32_t num_layers;  /* L >= 1                                                      */
-  uint64_t tile_bytes;  /* bytes of one block in one layer (K and V); multiple of 16   */
+  void*    base;                /* [device] 256-byte aligned                           */
+  uint32_t num_blocks;          /* NB, at most 2^24                                    */
+  uint32_t num_layers;          /* L >= 1                                              */
+  uint64_t tile_bytes;          /* one block in one layer (K and V); multiple of 16    */
+  uint64_t layer_stride_bytes;  /* 0 = block-major, else bytes between layer slabs     */
 } kv_pool_desc;
 
 /* Device-resident result header of a plan (32 bytes). */
@@ -111,7 +121,8 @@ int kv_plan_bind(kv_plan* plan, void* workspace, size_t workspace_bytes,
  * KV_E_NOSPACE, n_moves = 0, and the other outputs are unspecified. */
 int kv_plan_reclaim(const uint64_t* live_in, const kv_plan* plan, void* stream);
 
-/* Block copy: for k < n_moves, block dst[k] <- block src[k] (block_bytes each).
+/* Block copy: for k < n_moves, block dst[k] <- block src[k] (block_bytes each;
+ * in a layer-major pool, tile by tile in every layer slab).
  * Source blocks keep their bytes; no byte at or above block `boundary` and no
  * byte of a non-destination block is written.  Does nothing unless
  * state.status == KV_OK.  A move with src < boundary, src >= NB or dst >=
@@ -128,6 +139,7 @@ typedef struct kv_compact_tuning {
   uint32_t chunk_bytes;    /* bytes per work ticket; multiple of 4096 (default 65536)    */
   uint32_t flags;          /* bit 0: plain (cached) instead of non-temporal accesses;
                               bit 1: static grid-stride order instead of tickets;
+                              bit 2: layer-major pools: move by move instead of slab by slab;
                               bits 4-7: 128-bit loads in flight per lane (1, 2, 4 or 8)  */
   uint32_t reserved;
 } kv_compact_tuning;
@@ -161,7 +173,11 @@ typedef struct wm_tensor {
  * pages", App. C, Fig. 4b step 3; host memory to GPU over the host link,
  * Sec. 4.1; a copy is issued as soon as its destination is ready, App. C).
  * The reclaimed region is bytes [boundary*block_bytes, num_blocks*block_bytes)
- * of the pool.  All extents are validated first (inside the region: else
+ * of the pool.  In a layer-major pool it is the L strips taken one after the
+ * other in layer order (strip l = region offsets [l*S, (l+1)*S), S =
+ * (num_blocks-boundary)*tile_bytes); an extent that would straddle two strips
+ * is not contiguous in memory and is refused with KV_E_TOOBIG.
+ * All extents are validated first (inside the region: else
  * KV_E_TOOBIG; pairwise disjoint: else KV_E_OVERLAP).  Then, on copy_stream:
  * wait for `compaction_done` (hipEvent_t recorded after kv_compact; NULL = no
  * wait, the caller has ordered the streams) and enqueue the host-to-device
@@ -190,6 +206,7 @@ typedef struct wm_piece {
  * at block boundaries; runs that lie wholly in free blocks become early pieces
  * until early_bytes (0 = 128 MiB) have been collected; all other bytes become
  * late pieces, one per tensor remainder run.  Host arithmetic only.
+ * Block-major pools only (KV_E_RANGE otherwise).
  * Writes at most `capacity` pieces to out [host] (early pieces first) and the
  * full count to *n_out; returns KV_E_TOOBIG if capacity is too small, and the
  * validation errors of weights_materialize. */
@@ -225,7 +242,8 @@ int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks,
  * weights_materialize relative to the old region: evicted[i] = 1 if it has a
  * byte inside the returned blocks (it is lost), else 0 and new_offset[i] is its
  * offset relative to the new region's start.  Host arithmetic only; evicted,
- * new_offset [host] have n_tensors entries.  Returns the number of evicted
+ * new_offset [host] have n_tensors entries.  Block-major pools only
+ * (KV_E_RANGE otherwise).  Returns the number of evicted
  * tensors, or KV_E_RANGE / KV_E_NULL / KV_E_TOOBIG (an extent outside the
  * old region). */
 int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint32_t new_boundary,

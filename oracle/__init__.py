@@ -60,6 +60,10 @@ def lib():
         L.oracle_remap.argtypes = [vp, u64, vp, u32]
         L.oracle_materialize.restype = ctypes.c_int
         L.oracle_materialize.argtypes = [vp, u64, u64, ctypes.POINTER(_Tensor), u32]
+        L.oracle_compact_layer_major.restype = ctypes.c_int
+        L.oracle_compact_layer_major.argtypes = [vp, u64, u32, u64, vp, vp, u32]
+        L.oracle_materialize_strips.restype = ctypes.c_int
+        L.oracle_materialize_strips.argtypes = [vp, u64, u32, u32, u32, u64, ctypes.POINTER(_Tensor), u32]
         L.oracle_grow.restype = ctypes.c_int64
         L.oracle_grow.argtypes = [u64, u32, u32, u32, ctypes.POINTER(_Tensor), u32, vp, vp]
         L.oracle_reserve_blocks.restype = ctypes.c_int64
@@ -116,6 +120,32 @@ def compact(pool: np.ndarray, block_bytes: int, p: Plan) -> None:
                               _p(dst) if p.n_moves else None, p.n_moves)
     if rc != OK:
         raise ValueError(f"oracle_compact: error {rc}")
+
+
+def compact_layer_major(pool: np.ndarray, tile_bytes: int, num_layers: int, layer_stride: int, p: Plan) -> None:
+    """In place on a uint8 host pool laid out as num_layers slabs of layer_stride bytes."""
+    assert pool.dtype == np.uint8 and pool.size >= (num_layers - 1) * layer_stride + p.num_blocks * tile_bytes
+    if p.status != OK or p.n_moves == 0:
+        return
+    src = np.ascontiguousarray(p.src)
+    dst = np.ascontiguousarray(p.dst)
+    rc = lib().oracle_compact_layer_major(_p(pool), tile_bytes, num_layers, layer_stride, _p(src), _p(dst), p.n_moves)
+    if rc != OK:
+        raise ValueError(f"oracle_compact_layer_major: error {rc}")
+
+
+def materialize_strips(pool: np.ndarray, tile_bytes: int, num_layers: int, num_blocks: int, boundary: int,
+                       layer_stride: int, tensors) -> int:
+    """tensors: iterable of (uint8 host array, region offset).  Returns the oracle's status code."""
+    tensors = list(tensors)
+    arr = (_Tensor * max(1, len(tensors)))()
+    keep = []
+    for i, (buf, off) in enumerate(tensors):
+        buf = np.ascontiguousarray(buf).view(np.uint8).reshape(-1)
+        keep.append(buf)
+        arr[i] = _Tensor(buf.ctypes.data if buf.size else None, buf.size, off)
+    return int(lib().oracle_materialize_strips(_p(pool), tile_bytes, num_layers, num_blocks, boundary,
+                                               layer_stride, arr, len(tensors)))
 
 
 def remap(tables: np.ndarray, p: Plan) -> int:

@@ -132,7 +132,7 @@ int oracle_materialize(uint8_t* pool, uint64_t pool_bytes, uint64_t region_offse
     for (uint32_t j = i + 1; j < n_tensors; ++j) {
       const uint64_t a0 = tensors[i].dst_offset, a1 = a0 + tensors[i].bytes;
       const uint64_t b0 = tensors[j].dst_offset, b1 = b0 + tensors[j].bytes;
-      if (a0 < b1 && b0 < a1) return ORACLE_E_OVERLAP;
+      if (a0 < a1 && b0 < b1 && a0 < b1 && b0 < a1) return ORACLE_E_OVERLAP;  // an empty extent holds no byte
     }
   for (uint32_t i = 0; i < n_tensors; ++i)
     std::memcpy(pool + region_offset + tensors[i].dst_offset, tensors[i].host_ptr, tensors[i].bytes);
@@ -155,6 +155,52 @@ int64_t oracle_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks, ui
   if (R * B < numerator) ++R;
   if (R > C) R = C;
   return (int64_t)R;
+}
+
+// Block copy in a layer-major pool: layer l's tile of block i is tile_bytes
+// bytes at l*layer_stride + i*tile_bytes.  A block move is one tile copy per layer.
+int oracle_compact_layer_major(uint8_t* pool, uint64_t tile_bytes, uint32_t num_layers,
+                               uint64_t layer_stride, const int32_t* src, const int32_t* dst,
+                               uint32_t n_moves) {
+  if (!pool || (n_moves && (!src || !dst))) return ORACLE_E_NULL;
+  for (uint32_t k = 0; k < n_moves; ++k)
+    for (uint32_t l = 0; l < num_layers; ++l) {
+      uint8_t* slab = pool + (uint64_t)l * layer_stride;
+      std::memcpy(slab + (uint64_t)dst[k] * tile_bytes, slab + (uint64_t)src[k] * tile_bytes, tile_bytes);
+    }
+  return ORACLE_OK;
+}
+
+// Weight copy into a layer-major pool.  The reclaimed space is one strip per
+// layer slab, bytes [boundary*tile_bytes, num_blocks*tile_bytes) of the slab;
+// region offsets count through strip 0, then strip 1, ...  A tensor must lie
+// inside one strip (it has to be contiguous in memory).
+int oracle_materialize_strips(uint8_t* pool, uint64_t tile_bytes, uint32_t num_layers,
+                              uint32_t num_blocks, uint32_t boundary, uint64_t layer_stride,
+                              const oracle_tensor* tensors, uint32_t n_tensors) {
+  if (!pool || (n_tensors && !tensors)) return ORACLE_E_NULL;
+  if (boundary > num_blocks) return ORACLE_E_RANGE;
+  const uint64_t strip = (uint64_t)(num_blocks - boundary) * tile_bytes;
+  const uint64_t region_bytes = strip * num_layers;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const oracle_tensor& t = tensors[i];
+    if (t.bytes && !t.host_ptr) return ORACLE_E_NULL;
+    if (t.dst_offset > region_bytes || t.bytes > region_bytes - t.dst_offset) return ORACLE_E_TOOBIG;
+    if (t.bytes && (t.dst_offset / strip != (t.dst_offset + t.bytes - 1) / strip)) return ORACLE_E_TOOBIG;
+  }
+  for (uint32_t i = 0; i < n_tensors; ++i)
+    for (uint32_t j = i + 1; j < n_tensors; ++j) {
+      const uint64_t a0 = tensors[i].dst_offset, a1 = a0 + tensors[i].bytes;
+      const uint64_t b0 = tensors[j].dst_offset, b1 = b0 + tensors[j].bytes;
+      if (a0 < a1 && b0 < b1 && a0 < b1 && b0 < a1) return ORACLE_E_OVERLAP;  // an empty extent holds no byte
+    }
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const oracle_tensor& t = tensors[i];
+    if (!t.bytes) continue;
+    const uint64_t layer = t.dst_offset / strip, within = t.dst_offset % strip;
+    std::memcpy(pool + layer * layer_stride + (uint64_t)boundary * tile_bytes + within, t.host_ptr, t.bytes);
+  }
+  return ORACLE_OK;
 }
 
 // Reverse switch (Sec. 3.3: weights are evicted when the reserve runs short).

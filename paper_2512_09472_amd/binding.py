@@ -42,7 +42,8 @@ class WarmKVError(RuntimeError):
 
 
 class kv_pool_desc(Structure):
-    _fields_ = [("base", c_void_p), ("num_blocks", c_uint32), ("num_layers", c_uint32), ("tile_bytes", c_uint64)]
+    _fields_ = [("base", c_void_p), ("num_blocks", c_uint32), ("num_layers", c_uint32), ("tile_bytes", c_uint64),
+                ("layer_stride_bytes", c_uint64)]
 
 
 class kv_plan_state(Structure):
@@ -141,8 +142,9 @@ def _check(fn: str, rc: int) -> None:
         raise WarmKVError(fn, rc)
 
 
-def pool_desc(base, num_blocks: int, num_layers: int, tile_bytes: int) -> kv_pool_desc:
-    return kv_pool_desc(_ptr(base), num_blocks, num_layers, tile_bytes)
+def pool_desc(base, num_blocks: int, num_layers: int, tile_bytes: int, layer_stride_bytes: int = 0) -> kv_pool_desc:
+    """layer_stride_bytes = 0: block-major pool; otherwise layer-major with that slab stride."""
+    return kv_pool_desc(_ptr(base), num_blocks, num_layers, tile_bytes, layer_stride_bytes)
 
 
 def kv_plan_workspace_bytes(num_blocks: int, boundary: int) -> int:

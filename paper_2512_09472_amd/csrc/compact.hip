@@ -4,7 +4,8 @@
 // "map the physical pages of unused KV blocks to the new model's slot"
 // (App. C, Fig. 4b step 2): here the unused space is made contiguous instead.
 //
-// Shape.  The work list is (move, chunk) units of 64 KiB in list order.  One
+// Shape.  The work list is (move, chunk) units of 64 KiB in list order (in a
+// layer-major pool a move is one tile per layer slab: (move, layer, chunk)).  One
 // workgroup per compute unit stays resident and draws units from a single
 // device-wide ticket counter, so at any moment the 256 workgroups stream one
 // narrow, advancing window (about 16 MiB of sources and as much of
@@ -42,34 +43,52 @@ __device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
   else *p = v;
 }
 
+// A move copies `segs` contiguous segments of seg_bytes each: the whole block
+// in a block-major pool (segs = 1), one tile per layer slab in a layer-major
+// pool (segs = L).  Segment g of block i starts at i*block_stride + g*seg_stride.
 struct CopyArgs {
   uint8_t* base;
-  uint64_t block_bytes;
+  uint64_t block_stride;
+  uint64_t seg_stride;
+  uint64_t seg_bytes;
   const int32_t* src;
   const int32_t* dst;
   kv_plan_state* state;
   uint32_t num_blocks;
   uint32_t boundary;
   uint32_t chunk_bytes;
-  uint32_t chunks_per_block;
+  uint32_t chunks_per_seg;
+  uint32_t units_per_move;  // segs * chunks_per_seg
+  uint32_t seg_outer;       // unit order: 1 = segment-major (layer by layer), 0 = move-major
 };
 
-// Copy unit u = (move k, chunk c).  u is wavefront-uniform.
+// Copy unit u = (move k, segment g, chunk c).  u is wavefront-uniform.
 template <int UNROLL, bool NT>
-__device__ __forceinline__ void copy_unit(const CopyArgs& a, uint32_t u, uint32_t tid) {
+__device__ __forceinline__ void copy_unit(const CopyArgs& a, uint32_t n_moves, uint32_t u, uint32_t tid) {
   constexpr uint32_t kStep = kRowBytes * UNROLL;  // bytes per workgroup per inner iteration
-  const uint32_t k = u / a.chunks_per_block;
-  const uint32_t c = u - k * a.chunks_per_block;
+  uint32_t k, g, c;
+  if (a.seg_outer) {  // all moves of segment (layer) 0, then of segment 1, ...
+    const uint32_t per_seg = n_moves * a.chunks_per_seg;
+    g = u / per_seg;
+    const uint32_t r = u - g * per_seg;
+    k = r / a.chunks_per_seg;
+    c = r - k * a.chunks_per_seg;
+  } else {            // all segments of move 0, then of move 1, ...
+    k = u / a.units_per_move;
+    const uint32_t r = u - k * a.units_per_move;
+    g = r / a.chunks_per_seg;
+    c = r - g * a.chunks_per_seg;
+  }
   const uint32_t s = (uint32_t)a.src[k], d = (uint32_t)a.dst[k];
   if (s < a.boundary || s >= a.num_blocks || d >= a.boundary) {  // never true for a planner-made plan
     if (tid == 0) atomicExch(&a.state->status, KV_E_BADPLAN);
     return;
   }
-  const uint64_t off = (uint64_t)c * a.chunk_bytes;
-  const uint64_t left = a.block_bytes - off;
+  const uint64_t off = (uint64_t)g * a.seg_stride + (uint64_t)c * a.chunk_bytes;
+  const uint64_t left = a.seg_bytes - (uint64_t)c * a.chunk_bytes;
   const uint32_t len = left < a.chunk_bytes ? (uint32_t)left : a.chunk_bytes;
-  const u32x4* __restrict__ sp = (const u32x4*)(a.base + (uint64_t)s * a.block_bytes + off);
-  u32x4* __restrict__ dp = (u32x4*)(a.base + (uint64_t)d * a.block_bytes + off);
+  const u32x4* __restrict__ sp = (const u32x4*)(a.base + (uint64_t)s * a.block_stride + off);
+  u32x4* __restrict__ dp = (u32x4*)(a.base + (uint64_t)d * a.block_stride + off);
 
   uint32_t done = 0;
   for (; done + kStep <= len; done += kStep) {  // full rows, no bounds checks
@@ -89,8 +108,8 @@ template <int UNROLL, bool NT>
 __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a) {
   // No early return: every workgroup must draw its one out-of-range ticket and
   // sign out below, or the counters would not return to zero.
-  const uint32_t n_units =
-      a.state->status == KV_OK ? a.state->n_moves * a.chunks_per_block : 0u;  // host checked: fits 31 bits
+  const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
+  const uint32_t n_units = n_moves * a.units_per_move;  // host checked: fits 31 bits
   const uint32_t tid = threadIdx.x;
   __shared__ uint32_t s_ticket[2];
   if (tid == 0) s_ticket[0] = atomicAdd(&a.state->ticket, 1u);
@@ -101,7 +120,7 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
     if (u >= n_units) break;
     // The other slot was last read before the previous barrier: free to refill.
     if (tid == 0) s_ticket[slot ^ 1u] = atomicAdd(&a.state->ticket, 1u);
-    copy_unit<UNROLL, NT>(a, u, tid);
+    copy_unit<UNROLL, NT>(a, n_moves, u, tid);
     __syncthreads();
     slot ^= 1u;
   }
@@ -120,8 +139,9 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
 template <int UNROLL, bool NT>
 __global__ __launch_bounds__(kCopyThreads) void compact_static_kernel(CopyArgs a) {
   if (a.state->status != KV_OK) return;
-  const uint32_t n_units = a.state->n_moves * a.chunks_per_block;
-  for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) copy_unit<UNROLL, NT>(a, u, threadIdx.x);
+  const uint32_t n_moves = a.state->n_moves;
+  const uint32_t n_units = n_moves * a.units_per_move;
+  for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) copy_unit<UNROLL, NT>(a, n_moves, u, threadIdx.x);
 }
 
 template <int UNROLL, bool NT>
@@ -157,12 +177,37 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
                                      : (chunk >= 8 * kRowBytes ? 8u : (chunk >= 4 * kRowBytes ? 4u : (chunk >= 2 * kRowBytes ? 2u : 1u)));
   if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return KV_E_RANGE;
 
+  const bool layer_major = pool->layer_stride_bytes != 0;
+  if (layer_major && (pool->layer_stride_bytes % 256u != 0 ||
+                      pool->layer_stride_bytes < (uint64_t)pool->num_blocks * pool->tile_bytes))
+    return KV_E_RANGE;
   if (plan->capacity == 0 || pool->num_blocks == 0) return KV_OK;  // nothing can move
   if (pool->base == nullptr || plan->src == nullptr || plan->dst == nullptr) return KV_E_NULL;
   if (((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
-  const uint64_t block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
-  const uint64_t chunks_per_block = (block_bytes + chunk - 1) / chunk;
-  if (chunks_per_block * plan->capacity >= (1ull << 31)) return KV_E_RANGE;  // unit ids are 32-bit
+
+  CopyArgs a;
+  a.base = (uint8_t*)pool->base;
+  if (layer_major) {
+    a.block_stride = pool->tile_bytes;
+    a.seg_stride = pool->layer_stride_bytes;
+    a.seg_bytes = pool->tile_bytes;
+  } else {
+    a.block_stride = (uint64_t)pool->num_layers * pool->tile_bytes;
+    a.seg_stride = 0;
+    a.seg_bytes = a.block_stride;
+  }
+  const uint64_t segs = layer_major ? pool->num_layers : 1u;
+  const uint64_t chunks_per_seg = (a.seg_bytes + chunk - 1) / chunk;
+  if (segs * chunks_per_seg * plan->capacity >= (1ull << 31)) return KV_E_RANGE;  // unit ids are 32-bit
+  a.src = plan->src;
+  a.dst = plan->dst;
+  a.state = plan->state;
+  a.num_blocks = plan->num_blocks;
+  a.boundary = plan->boundary;
+  a.chunk_bytes = chunk;
+  a.chunks_per_seg = (uint32_t)chunks_per_seg;
+  a.units_per_move = (uint32_t)(segs * chunks_per_seg);
+  a.seg_outer = (layer_major && (flags & 4u) == 0) ? 1u : 0u;
 
   if (workgroups == 0) {  // one resident workgroup per compute unit
     int device = 0, cus = 0;
@@ -171,17 +216,6 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
       return KV_E_HIP;
     workgroups = (uint32_t)cus;
   }
-
-  CopyArgs a;
-  a.base = (uint8_t*)pool->base;
-  a.block_bytes = block_bytes;
-  a.src = plan->src;
-  a.dst = plan->dst;
-  a.state = plan->state;
-  a.num_blocks = plan->num_blocks;
-  a.boundary = plan->boundary;
-  a.chunk_bytes = chunk;
-  a.chunks_per_block = (uint32_t)chunks_per_block;
 
   const bool nt = (flags & 1u) == 0;
   const bool tickets = (flags & 2u) == 0;

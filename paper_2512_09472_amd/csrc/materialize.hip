@@ -23,23 +23,49 @@ constexpr uint64_t kDefaultEarly = 128ull << 20;  // early bytes when the caller
                                                  // costs ~10 us of request overhead, so more loses
 
 struct Region {
-  uint64_t block_bytes, offset, bytes;
+  bool layer_major;
+  uint64_t block_bytes;   // block-major: bytes per block
+  uint64_t offset;        // block-major: first byte of the region; layer-major: first byte of a strip in its slab
+  uint64_t bytes;         // size of the region (all strips together)
+  uint64_t strip_bytes;   // layer-major: bytes per strip
+  uint64_t layer_stride;
 };
 
-// Every extent inside the region and pairwise disjoint, before any byte moves.
+// Device address of region offset `at` (validated to lie inside the region).
+uint8_t* region_address(const kv_pool_desc* pool, const Region& r, uint64_t at) {
+  uint8_t* base = (uint8_t*)pool->base;
+  if (!r.layer_major) return base + r.offset + at;
+  const uint64_t strip = r.strip_bytes ? at / r.strip_bytes : 0;
+  return base + strip * r.layer_stride + r.offset + (at - strip * r.strip_bytes);
+}
+
+// Every extent inside the region, contiguous in memory and pairwise disjoint,
+// before any byte moves.
 int validate(const kv_pool_desc* pool, uint32_t boundary, const wm_tensor* tensors, uint32_t n_tensors,
              Region* region) {
   if (pool == nullptr || (n_tensors != 0 && tensors == nullptr)) return KV_E_NULL;
   if (boundary > pool->num_blocks) return KV_E_RANGE;
+  region->layer_major = pool->layer_stride_bytes != 0;
+  region->layer_stride = pool->layer_stride_bytes;
   region->block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
-  region->offset = (uint64_t)boundary * region->block_bytes;
-  region->bytes = (uint64_t)(pool->num_blocks - boundary) * region->block_bytes;
+  if (region->layer_major) {
+    if (pool->layer_stride_bytes < (uint64_t)pool->num_blocks * pool->tile_bytes) return KV_E_RANGE;
+    region->offset = (uint64_t)boundary * pool->tile_bytes;
+    region->strip_bytes = (uint64_t)(pool->num_blocks - boundary) * pool->tile_bytes;
+    region->bytes = region->strip_bytes * pool->num_layers;
+  } else {
+    region->offset = (uint64_t)boundary * region->block_bytes;
+    region->strip_bytes = 0;
+    region->bytes = (uint64_t)(pool->num_blocks - boundary) * region->block_bytes;
+  }
   std::vector<uint32_t> order;
   order.reserve(n_tensors);
   for (uint32_t i = 0; i < n_tensors; ++i) {
     const wm_tensor& t = tensors[i];
     if (t.dst_offset > region->bytes || t.bytes > region->bytes - t.dst_offset) return KV_E_TOOBIG;
     if (t.bytes == 0) continue;
+    if (region->layer_major && t.dst_offset % region->strip_bytes + t.bytes > region->strip_bytes)
+      return KV_E_TOOBIG;  // would straddle two strips
     if (t.host_ptr == nullptr) return KV_E_NULL;
     order.push_back(i);
   }
@@ -116,9 +142,10 @@ extern "C" int weights_materialize(const kv_pool_desc* pool, uint32_t boundary, 
     rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
     if (rc != KV_OK) return rc;
   }
-  uint8_t* region = (uint8_t*)pool->base + r.offset;
   for (uint32_t i = 0; i < n_tensors; ++i) {  // caller's order
-    rc = enqueue(region + tensors[i].dst_offset, (const uint8_t*)tensors[i].host_ptr, tensors[i].bytes, s);
+    if (tensors[i].bytes == 0) continue;
+    rc = enqueue(region_address(pool, r, tensors[i].dst_offset), (const uint8_t*)tensors[i].host_ptr,
+                 tensors[i].bytes, s);
     if (rc != KV_OK) return rc;
   }
   return KV_OK;
@@ -133,7 +160,7 @@ extern "C" int weights_materialize_schedule(const kv_pool_desc* pool, uint32_t b
   if (rc != KV_OK) return rc;
   if (n_out == nullptr || (capacity != 0 && out == nullptr)) return KV_E_NULL;
   if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
-  if (r.block_bytes == 0) return KV_E_RANGE;
+  if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
   std::vector<wm_piece> early, late;
   schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
   const size_t total = early.size() + late.size();
@@ -153,7 +180,7 @@ extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t 
   int rc = validate(pool, boundary, tensors, n_tensors, &r);
   if (rc != KV_OK) return rc;
   if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
-  if (r.block_bytes == 0) return KV_E_RANGE;
+  if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
   std::vector<wm_piece> early, late;
   schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
   hipStream_t s = (hipStream_t)copy_stream;

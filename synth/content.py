@@ -90,17 +90,20 @@ def _load():
         lib.synth_fill.restype = ctypes.c_int
         lib.synth_fill.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64,
                                    ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int64,
-                                   ctypes.c_void_p, ctypes.c_void_p]
+                                   ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
         _lib = lib
     return _lib
 
 
 def fill_device(dst_ptr: int, n_items: int, item_bytes: int, seed: int, *,
-                cids_ptr: int = 0, cid0: int = 0, table_ptr: int = 0, stream: int = 0) -> None:
+                cids_ptr: int = 0, cid0: int = 0, table_ptr: int = 0, byte_offset: int = 0,
+                stream: int = 0) -> None:
     """Fill device memory at ``dst_ptr`` with n_items items.  Item i has content
     id ``cids[i]`` (device int32 array) when ``cids_ptr`` is non-zero, else
-    ``cid0 + i``.  ``table_ptr`` is a device uint16[65536] table or 0 for raw bytes."""
+    ``cid0 + i``; it receives bytes [byte_offset, byte_offset + item_bytes) of that
+    content.  ``table_ptr`` is a device uint16[65536] table or 0 for raw bytes."""
+    assert byte_offset % 8 == 0
     rc = _load().synth_fill(dst_ptr, n_items, item_bytes, seed & MASK64, cids_ptr, cid0,
-                            table_ptr, stream)
+                            table_ptr, byte_offset // 8, stream)
     if rc != 0:
         raise RuntimeError(f"synth_fill failed with code {rc}")

@@ -28,12 +28,12 @@ typedef unsigned long long u64x2 __attribute__((ext_vector_type(2)));
 __global__ __launch_bounds__(256) void fill_kernel(u64x2* __restrict__ dst, uint64_t n_items,
                                                    uint64_t units_per_item, uint64_t seed,
                                                    const int32_t* __restrict__ cids, int64_t cid0,
-                                                   const uint16_t* __restrict__ table) {
+                                                   const uint16_t* __restrict__ table, uint64_t word0) {
   const uint64_t total = n_items * units_per_item;
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   for (uint64_t u = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; u < total; u += stride) {
     const uint64_t item = u / units_per_item;
-    const uint64_t w = (u - item * units_per_item) * 2;
+    const uint64_t w = word0 + (u - item * units_per_item) * 2;
     const int64_t cid = cids ? (int64_t)cids[item] : cid0 + (int64_t)item;
     const uint64_t base = mix64(seed + (uint64_t)(cid + 1) * kGolden);
     u64x2 v;
@@ -46,10 +46,12 @@ __global__ __launch_bounds__(256) void fill_kernel(u64x2* __restrict__ dst, uint
 }  // namespace
 
 // dst, cids, table: device pointers.  item_bytes must be a multiple of 16 and
-// dst 16-byte aligned.  Returns 0, or a non-zero code on a bad argument or a
-// failed launch.
+// dst 16-byte aligned.  Each item receives item_bytes of its content starting
+// at 64-bit word `word0` (so a slice of a larger item can be generated alone).
+// Returns 0, or a non-zero code on a bad argument or a failed launch.
 extern "C" int synth_fill(void* dst, uint64_t n_items, uint64_t item_bytes, uint64_t seed,
-                          const int32_t* cids, int64_t cid0, const uint16_t* table, void* stream) {
+                          const int32_t* cids, int64_t cid0, const uint16_t* table, uint64_t word0,
+                          void* stream) {
   if (dst == nullptr || (item_bytes & 15) != 0 || ((uintptr_t)dst & 15) != 0) return 1;
   if (n_items == 0 || item_bytes == 0) return 0;
   const uint64_t units = item_bytes / 16;
@@ -57,6 +59,6 @@ extern "C" int synth_fill(void* dst, uint64_t n_items, uint64_t item_bytes, uint
   uint64_t blocks = (total + 255) / 256;
   if (blocks > 256 * 32) blocks = 256 * 32;
   hipLaunchKernelGGL(fill_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream,
-                     (u64x2*)dst, n_items, units, seed, cids, cid0, table);
+                     (u64x2*)dst, n_items, units, seed, cids, cid0, table, word0);
   return hipGetLastError() == hipSuccess ? 0 : 2;
 }

@@ -31,7 +31,7 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_struct_sizes_match_the_header():
-    assert ctypes.sizeof(binding.kv_pool_desc) == 24
+    assert ctypes.sizeof(binding.kv_pool_desc) == 32
     assert ctypes.sizeof(binding.kv_plan_state) == 32
     assert ctypes.sizeof(binding.kv_plan) == 56
     assert ctypes.sizeof(binding.kv_compact_tuning) == 16

@@ -123,6 +123,53 @@ def test_full_size_reclaim(oracle, index):
     torch.cuda.empty_cache()
 
 
+def test_full_size_layer_major_reclaim(oracle):
+    """The 8B-shaped pool kept layer-major (32 slabs of 1.25 GiB): every slab is checked in full
+    against the oracle's plan, slab by slab, with the device generator."""
+    cfg = CONFIGS[1]
+    free_b, _ = torch.cuda.mem_get_info()
+    if free_b < cfg.pool_bytes + (4 << 30):
+        pytest.skip("not enough device memory")
+    w = make_workload(cfg)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    table_d = gh.to_dev(gh.content_table(cfg))
+    tile, nb, layers = cfg.tile_bytes, cfg.num_blocks, cfg.num_layers
+    stride = nb * tile
+    pool_t = torch.empty(layers * stride, dtype=torch.uint8, device=gh.dev())
+    for l in range(layers):
+        content.fill_device(pool_t.data_ptr() + l * stride, nb, tile, cfg.seed, table_ptr=table_d.data_ptr(),
+                            byte_offset=l * tile)
+    pool = wk.pool_desc(pool_t, nb, layers, tile, stride)
+    dp = gh.DevicePlan(nb, cfg.boundary)
+    live_d = gh.to_dev(w.live)
+    torch.cuda.synchronize()
+    wk.kv_plan_reclaim(live_d, dp.plan)
+    wk.kv_compact(pool, dp.plan)
+    torch.cuda.synchronize()
+    st, src, dst, new_id, live_out = dp.results()
+    assert st.status == 0 and np.array_equal(src, p.src) and np.array_equal(dst, p.dst)
+    cid = np.arange(nb, dtype=np.int32)
+    cid[p.dst] = p.src
+    cid_d = gh.to_dev(cid)
+    scratch = torch.empty(stride, dtype=torch.uint8, device=gh.dev())
+    for l in range(layers):
+        content.fill_device(scratch.data_ptr(), nb, tile, cfg.seed, cids_ptr=cid_d.data_ptr(),
+                            table_ptr=table_d.data_ptr(), byte_offset=l * tile)
+        assert torch.equal(pool_t[l * stride:(l + 1) * stride], scratch), f"slab {l}"
+    # sampled tiles against the oracle's layer-major copy on a two-block host pool
+    rs = np.random.default_rng(1)
+    table = gh.content_table(cfg)
+    for k in rs.choice(p.n_moves, size=6, replace=False).tolist():
+        l = int(rs.integers(0, layers))
+        s_id, d_id = int(p.src[k]), int(p.dst[k])
+        mini = np.zeros(2 * tile, dtype=np.uint8)             # one slab of two blocks: [dst, src]
+        mini[tile:] = content.item_bytes_host(cfg.seed, s_id, tile, table, byte_offset=l * tile)
+        one = oracle.Plan(0, np.array([1], np.int32), np.array([0], np.int32), None, None, 1, 2, 1)
+        oracle.compact_layer_major(mini, tile, 1, 2 * tile, one)
+        got = pool_t[l * stride + d_id * tile: l * stride + (d_id + 1) * tile].cpu().numpy()
+        assert np.array_equal(got, mini[:tile]), (k, l)
+
+
 def test_full_size_reclaim_with_weights(oracle):
     """Third configuration: the 8B-shaped pool plus 225 bf16 tensors (15 009 316 864 B)
     streamed from pinned host memory into the reclaimed region, overlapped with compaction."""

@@ -386,3 +386,71 @@ def test_vmm_variant_lends_pages_without_moving_bytes():
     finally:
         torch.cuda.synchronize()
         wk.kv_vmm_pool_destroy(pool)
+
+
+LAYER_MAJOR = {
+    "lm_small": (CONFIGS[1].scaled(num_blocks=640, num_layers=3, num_seqs=40), 0),
+    "lm_padded_slabs": (CONFIGS[3].scaled(num_blocks=1536, num_layers=4, num_seqs=128), 4096),
+    "lm_ragged_tile": (CONFIGS[1].scaled(num_blocks=900, num_layers=5, kv_heads=3, head_dim=40, num_seqs=40), 256),
+    "lm_tiny_tile": (CONFIGS[4].scaled(num_blocks=2048, num_layers=6, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512), 0),
+}
+
+
+def _layer_major_pool(cfg, pad):
+    """Host pool [L][stride]: slab l holds bytes [l*tile, (l+1)*tile) of every block's content."""
+    table = gh.content_table(cfg)
+    tile, nb, layers = cfg.tile_bytes, cfg.num_blocks, cfg.num_layers
+    stride = nb * tile + pad
+    pool = np.full(layers * stride, 0x5A, dtype=np.uint8)
+    slabs = pool.reshape(layers, stride)
+    for i in range(nb):
+        blk = content.item_bytes_host(cfg.seed, i, cfg.block_bytes, table).reshape(layers, tile)
+        slabs[:, i * tile:(i + 1) * tile] = blk
+    return pool, stride
+
+
+@pytest.mark.parametrize("name", list(LAYER_MAJOR))
+def test_layer_major_reclaim_matches_oracle(oracle, name):
+    cfg, pad = LAYER_MAJOR[name]
+    w = make_workload(cfg)
+    pool0, stride = _layer_major_pool(cfg, pad)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    assert p.status == 0 and p.n_moves > 0
+    want = pool0.copy()
+    oracle.compact_layer_major(want, cfg.tile_bytes, cfg.num_layers, stride, p)
+    # weights into the strips: one tensor per strip start, one that ends exactly at a strip end
+    strip = (cfg.num_blocks - cfg.boundary) * cfg.tile_bytes
+    sizes = [min(strip, 4096 * 3), min(strip, 100 * 16)]
+    offs = [0, (cfg.num_layers - 1) * strip + strip - sizes[1]]
+    hosts = []
+    for i, sz in enumerate(sizes):
+        h = torch.empty(sz, dtype=torch.uint8, pin_memory=True)
+        h.numpy()[:] = content.item_bytes_host(0xABCD, i, -(-sz // 8) * 8, None)[:sz]
+        hosts.append(h)
+    assert oracle.materialize_strips(want, cfg.tile_bytes, cfg.num_layers, cfg.num_blocks, cfg.boundary, stride,
+                                     [(h.numpy(), o) for h, o in zip(hosts, offs)]) == 0
+    for tuning in (None, dict(chunk_bytes=4096, flags=1 << 4), dict(workgroups=3000, chunk_bytes=16384, flags=4 << 4),
+                   dict(workgroups=512, chunk_bytes=32768, flags=(2 << 4) | 2), dict(flags=4),
+                   dict(workgroups=100, chunk_bytes=8192, flags=(2 << 4) | 2 | 4)):
+        _say(f"[layer-major] {name} tile={cfg.tile_bytes} L={cfg.num_layers} NB={cfg.num_blocks} pad={pad} tuning={tuning}")
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, stride)
+        dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+        live_dev = gh.to_dev(w.live)
+        wk.kv_plan_reclaim(live_dev, dp.plan)
+        if tuning:
+            wk.kv_compact_launch(pool, dp.plan, **tuning)
+        else:
+            wk.kv_compact(pool, dp.plan)
+        wk.weights_materialize(pool, cfg.boundary, [(h, h.numel(), o) for h, o in zip(hosts, offs)])
+        torch.cuda.synchronize()
+        _compare_plan(dp, p)
+        assert np.array_equal(pool_dev.cpu().numpy(), want)
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, stride)
+    with pytest.raises(wk.WarmKVError) as e:      # an extent across two strips is not contiguous in memory
+        wk.weights_materialize(pool, cfg.boundary, [(hosts[0], 32, strip - 16)])
+    assert e.value.code == wk.KV_E_TOOBIG
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.kv_compact(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes,
+                                   cfg.num_blocks * cfg.tile_bytes - 256), dp.plan)   # slabs would overlap
+    assert e.value.code == wk.KV_E_RANGE

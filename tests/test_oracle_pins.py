@@ -254,6 +254,49 @@ def test_materialize_rejects_before_writing(oracle):
     assert oracle.materialize(pool, b * bb, [(ok, 112), (ok, 127)]) in (oracle.E_TOOBIG, oracle.E_OVERLAP)
     assert np.array_equal(pool, ref)
     assert oracle.materialize(pool, b * bb, [(ok, 0), (ok, 16), (ok, 112)]) == 0
+    assert oracle.materialize(pool, b * bb, [(ok, 0), (np.zeros(0, np.uint8), 5)]) == 0   # an empty extent overlaps nothing
+
+
+def test_layer_major_compact_is_the_block_major_one_under_a_transpose(oracle):
+    """A layer-major pool [L][NB][tile] is the block-major pool [NB][L][tile] with two axes
+    swapped; the block copy must commute with that swap (numpy transpose, pinned block-major oracle)."""
+    rs = np.random.default_rng(6)
+    for nb, b, layers, tile, pad in ((40, 22, 3, 16, 0), (130, 70, 5, 48, 256), (64, 32, 1, 32, 0)):
+        live = rs.random(nb) < 0.45
+        p = oracle.plan(bitmap_from_ids(np.flatnonzero(live), nb), nb, b)
+        assert p.status == 0 and p.n_moves > 0
+        stride = nb * tile + pad
+        lm = rs.integers(0, 256, layers * stride, dtype=np.uint8)
+        before = lm.copy()
+        slabs = lm.reshape(layers, stride)
+        bm = np.ascontiguousarray(slabs[:, :nb * tile].reshape(layers, nb, tile).transpose(1, 0, 2)).reshape(-1)
+        oracle.compact(bm, layers * tile, p)
+        want = before.copy().reshape(layers, stride)
+        want[:, :nb * tile] = bm.reshape(nb, layers, tile).transpose(1, 0, 2).reshape(layers, nb * tile)
+        oracle.compact_layer_major(lm, tile, layers, stride, p)
+        assert np.array_equal(lm, want.reshape(-1))
+        assert np.array_equal(lm.reshape(layers, stride)[:, nb * tile:], before.reshape(layers, stride)[:, nb * tile:]), "padding untouched"
+
+
+def test_materialize_strips_matches_slicing(oracle):
+    rs = np.random.default_rng(7)
+    nb, b, layers, tile, stride = 20, 12, 3, 32, 20 * 32 + 256
+    pool = rs.integers(0, 256, layers * stride, dtype=np.uint8)
+    strip = (nb - b) * tile
+    tensors = [(rs.integers(0, 256, 100, dtype=np.uint8), 0), (rs.integers(0, 256, strip, dtype=np.uint8), strip),
+               (rs.integers(0, 256, 7, dtype=np.uint8), 2 * strip + 249), (np.zeros(0, np.uint8), 3)]
+    want = pool.copy().reshape(layers, stride)
+    for buf, off in tensors:
+        layer, within = (off // strip, off % strip) if buf.size else (0, 0)
+        want[layer, b * tile + within: b * tile + within + buf.size] = buf
+    assert oracle.materialize_strips(pool, tile, layers, nb, b, stride, tensors) == 0
+    assert np.array_equal(pool, want.reshape(-1))
+    ref = pool.copy()
+    one = np.ones(10, np.uint8)
+    assert oracle.materialize_strips(pool, tile, layers, nb, b, stride, [(one, strip - 5)]) == oracle.E_TOOBIG   # straddles
+    assert oracle.materialize_strips(pool, tile, layers, nb, b, stride, [(one, 3 * strip - 9)]) == oracle.E_TOOBIG
+    assert oracle.materialize_strips(pool, tile, layers, nb, b, stride, [(one, 0), (one, 9)]) == oracle.E_OVERLAP
+    assert np.array_equal(pool, ref)
 
 
 def test_grow_hand_cases_and_byte_brute_force(oracle):

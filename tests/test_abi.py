@@ -215,3 +215,19 @@ def test_grow_matches_oracle_and_hand_cases(oracle):
             assert bool(ev[i]) == (b > 0 and first_byte_returned)
             if not ev[i] and b > 0:
                 assert no[i] == ono[i] == old * bb + o - new * bb
+
+
+def test_product_path_never_touches_the_oracle():
+    """The package and the HIP sources must not import, include or load anything of the CPU oracle."""
+    pkg = os.path.join(ROOT, "paper_2512_09472_amd")
+    for dirpath, _, files in os.walk(pkg):
+        if "_build" in dirpath or "__pycache__" in dirpath:
+            continue
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text.lower(), f"{f} mentions the oracle"
+    for f in ("warmkv.h",):
+        assert "oracle" not in open(os.path.join(ROOT, "include", f)).read().lower()
+    src = open(os.path.join(ROOT, "oracle", "warmkv_oracle.cpp")).read() + open(os.path.join(ROOT, "oracle", "__init__.py")).read()
+    assert "warmkv.h" not in src and "paper_2512_09472_amd" not in src and "import synth" not in src

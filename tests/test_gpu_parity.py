@@ -107,7 +107,8 @@ def test_device_fill_matches_host_generator():
 PLAN_CASES = [(1, 0, 1.0), (1, 1, 1.0), (63, 31, 0.4), (64, 64, 0.3), (65, 64, 0.5), (130, 70, 0.3),
               (1000, 999, 0.5), (4097, 2500, 0.5), (65536, 32768, 0.45), (65536, 65535, 0.5),
               (65537, 40001, 0.5), (70001, 33333, 0.4), (200000, 131072, 0.6), (200000, 77777, 0.35),
-              (300000, 0, 0.0), (300000, 300000, 0.7), (1 << 20, 600011, 0.5)]
+              (300000, 0, 0.0), (300000, 300000, 0.7), (1 << 20, 600011, 0.5),
+              (1 << 24, 9_000_001, 0.5)]     # the last one is the largest pool the planner accepts
 
 
 @pytest.mark.parametrize("nb,b,p_live", PLAN_CASES)
@@ -454,3 +455,60 @@ def test_layer_major_reclaim_matches_oracle(oracle, name):
         wk.kv_compact(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes,
                                    cfg.num_blocks * cfg.tile_bytes - 256), dp.plan)   # slabs would overlap
     assert e.value.code == wk.KV_E_RANGE
+
+
+def test_two_reclaims_on_two_streams_do_not_interfere(oracle):
+    """The library keeps no global state: two pools, two plans, two streams, interleaved calls."""
+    cfgs = [CONFIGS[1].scaled(num_blocks=1024, num_layers=4, num_seqs=64),
+            CONFIGS[4].scaled(num_blocks=3000, num_layers=3, num_seqs=700)]
+    runs = []
+    for cfg in cfgs:
+        w = make_workload(cfg)
+        pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+        p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+        want_pool, want_tables = pool0.copy(), w.tables.copy()
+        oracle.compact(want_pool, cfg.block_bytes, p)
+        oracle.remap(want_tables, p)
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        runs.append(dict(cfg=cfg, w=w, p=p, want_pool=want_pool, want_tables=want_tables, pool_dev=pool_dev,
+                         pool=wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes),
+                         dp=gh.DevicePlan(cfg.num_blocks, cfg.boundary), live_dev=gh.to_dev(w.live),
+                         tables_dev=torch.from_numpy(w.tables).to(gh.dev()), stream=torch.cuda.Stream()))
+    torch.cuda.synchronize()
+    for r in runs:
+        wk.kv_plan_reclaim(r["live_dev"], r["dp"].plan, r["stream"].cuda_stream)
+    for r in runs:
+        wk.kv_compact(r["pool"], r["dp"].plan, r["stream"].cuda_stream)
+    for r in reversed(runs):
+        wk.kv_remap_tables(r["tables_dev"], r["w"].tables.shape[0], r["w"].tables.shape[1], r["dp"].plan,
+                           r["stream"].cuda_stream)
+    torch.cuda.synchronize()
+    for r in runs:
+        _compare_plan(r["dp"], r["p"])
+        assert np.array_equal(r["tables_dev"].cpu().numpy(), r["want_tables"])
+        assert np.array_equal(r["pool_dev"].cpu().numpy(), r["want_pool"])
+
+
+def test_plan_can_be_reused_after_the_pool_changes(oracle):
+    """Plan, move, then plan again on the bitmap the first plan produced: nothing is left to move,
+    and a third plan after new allocations above the boundary moves exactly those."""
+    cfg = CONFIGS[1].scaled(num_blocks=2048, num_layers=2, num_seqs=64)
+    w = make_workload(cfg)
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    dp, tables_dev = gh.run_reclaim(cfg, w.live, w.tables, pool_dev)
+    st, src, dst, new_id, live_out = dp.results()
+    p1 = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    assert np.array_equal(live_out, p1.live_out)
+    dp2 = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    wk.kv_plan_reclaim(gh.to_dev(live_out), dp2.plan)
+    wk.kv_compact(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes), dp2.plan)
+    torch.cuda.synchronize()
+    assert dp2.state().n_moves == 0 and dp2.state().status == 0
+    grown = live_out.copy()
+    for j in (cfg.boundary, cfg.boundary + 65, cfg.num_blocks - 1):
+        grown[j // 64] |= np.uint64(1) << np.uint64(j % 64)
+    p3 = oracle.plan(grown, cfg.num_blocks, cfg.boundary)
+    wk.kv_plan_reclaim(gh.to_dev(grown), dp2.plan)          # same workspace, third use
+    _compare_plan(dp2, p3)
+    assert p3.n_moves == 3

@@ -179,7 +179,7 @@ def main():
 
     reclaimed_bytes = (cfg.num_blocks - cfg.boundary) * bb
     out = {
-        "metric": "kv_compaction_GBps_read_plus_write",
+        "metric": "KV compaction GB/s (read+write)",
         "value": round(rw_bytes / (ms_per_step * 1e-3) / 1e9, 2),
         "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

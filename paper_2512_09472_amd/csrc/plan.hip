@@ -12,6 +12,9 @@
 // gets its carry by reducing the words in front of it (a few KiB from L2)
 // instead of talking to its neighbours, and a tiny second kernel joins the two
 // lists into new_id.  With one workgroup everything is fused in one launch.
+// All outputs are produced in id order (ranks are monotone in ids), so even
+// the two lists are written nearly coalesced: a one-workgroup kernel lives on
+// one compute unit, and per-lane bit walks with strided stores cost it 3x.
 #include "common.h"
 
 namespace warmkv {
@@ -65,6 +68,22 @@ __device__ __forceinline__ uint64_t wave_sum(uint64_t v) {
   return v;
 }
 
+// The `count` lowest set bits of m (0 < count < popcount(m)).
+__device__ __forceinline__ uint64_t lowest_set_bits(uint64_t m, uint32_t count) {
+  uint64_t rest = m;
+  uint32_t pos = 0;  // becomes the position of the count-th (0-based) set bit
+#pragma unroll
+  for (uint32_t width = 32; width != 0; width >>= 1) {
+    const uint32_t c = (uint32_t)__popcll(rest & ((1ull << width) - 1ull));
+    if (count >= c) {
+      count -= c;
+      rest >>= width;
+      pos += width;
+    }
+  }
+  return m & ((1ull << pos) - 1ull);
+}
+
 template <bool FUSED>
 __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
     const uint64_t* __restrict__ live_in, uint32_t n_words, uint32_t num_blocks, uint32_t boundary,
@@ -74,7 +93,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
   __shared__ uint64_t s_wave[kWaves];
   __shared__ uint64_t s_carry[2][kWaves];
   __shared__ uint64_t s_live[kPlanThreads];
-  __shared__ uint32_t s_mrank[kPlanThreads];
+  __shared__ uint64_t s_rank[kPlanThreads];
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & (kWave - 1);
@@ -138,45 +157,78 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
   }
   if (!feasible) return;  // uniform over the whole grid: nothing else is written
 
-  // movers and free ids, each written at its rank
-  const uint32_t base_id = wi * 64u;
-  uint32_t m_rank = (uint32_t)(excl >> 32);
-  uint32_t a_rank = (uint32_t)excl;
+  // Everything below is written in id order, four consecutive ids (same bitmap
+  // word) per lane per pass.  Ranks grow with ids, so neighbouring lanes write
+  // neighbouring list entries: the src/dst lists come out (nearly) coalesced,
+  // which matters because this whole kernel runs on one compute unit.
   s_live[tid] = wb.live;
-  s_mrank[tid] = m_rank;
-  for (uint64_t bits = wb.mover; bits; bits &= bits - 1)
-    src[m_rank++] = (int32_t)(base_id + (uint32_t)__builtin_ctzll(bits));
-  uint64_t taken = 0;
-  for (uint64_t bits = wb.avail; bits && a_rank < n_moves; bits &= bits - 1) {
-    const uint32_t j = (uint32_t)__builtin_ctzll(bits);
-    dst[a_rank++] = (int32_t)(base_id + j);
-    taken |= 1ull << j;
+  s_rank[tid] = excl;  // movers before this word (high half), free ids before it (low half)
+  if (wi < n_words) {
+    // bitmap after the move: survivors below the boundary plus the free ids that get taken
+    const uint32_t a_rank = (uint32_t)excl;
+    uint64_t taken = 0;
+    if (a_rank < n_moves) {
+      const uint32_t want = n_moves - a_rank;
+      taken = want >= (uint32_t)__popcll(wb.avail) ? wb.avail : lowest_set_bits(wb.avail, want);
+    }
+    live_out[wi] = wb.keep | taken;
   }
-  if (wi < n_words) live_out[wi] = wb.keep | taken;
-
-  // Makes s_live/s_mrank visible and, in the fused shape, the whole dst list
-  // (all of it written by this workgroup).
   __syncthreads();
 
-  // dense id map, coalesced over this workgroup's 65 536 ids
   const uint32_t group_first_id = first_word * 64u;
-  for (uint32_t it = 0; it < 64u; ++it) {
-    const uint32_t local = it * kPlanThreads + tid;
-    const uint32_t id = group_first_id + local;
-    if (id >= num_blocks) break;
-    const uint32_t wl = local >> 6, bit = local & 63u;
-    const uint64_t w = s_live[wl];
-    int32_t out = -1;
-    if ((w >> bit) & 1ull) {
-      if (id < boundary) {
-        out = (int32_t)id;
-      } else if (FUSED) {
-        const uint64_t movers_before = w & ~low_mask((first_word + wl) * 64u, boundary) & ((1ull << bit) - 1ull);
-        out = dst[s_mrank[wl] + (uint32_t)__popcll(movers_before)];
+  const uint32_t first_pass_at_boundary = boundary > group_first_id ? (boundary - group_first_id) / (kPlanThreads * 4u) : 0u;
+  for (uint32_t it = 0; it < 16u; ++it) {
+    const uint32_t local = (it * kPlanThreads + tid) * 4u;
+    const uint32_t id0 = group_first_id + local;
+    if (id0 >= num_blocks) break;
+    const uint32_t wl = local >> 6, bit0 = local & 63u;
+    const uint64_t live = s_live[wl];
+    const uint64_t lo = low_mask(id0 - bit0, boundary);
+    const uint64_t valid = low_mask(id0 - bit0, num_blocks);
+    const uint64_t movers = live & ~lo, avail = ~live & lo & valid;
+    const uint64_t below = (1ull << bit0) - 1ull;
+    const uint64_t rank = s_rank[wl];
+    uint32_t m_rank = (uint32_t)(rank >> 32) + (uint32_t)__popcll(movers & below);
+    uint32_t a_rank = (uint32_t)rank + (uint32_t)__popcll(avail & below);
+    int32_t out[4];
+#pragma unroll
+    for (uint32_t e = 0; e < 4u; ++e) {
+      const uint32_t bit = bit0 + e;
+      const int32_t id = (int32_t)(id0 + e);
+      out[e] = -1;
+      if ((movers >> bit) & 1ull) {
+        src[m_rank++] = id;      // its new_id entry follows below (fused) or in join_kernel
+      } else if ((live >> bit) & 1ull) {
+        out[e] = id;             // live below the boundary: stays
+      } else if ((avail >> bit) & 1ull) {
+        if (a_rank < n_moves) dst[a_rank] = id;
+        ++a_rank;
       }
-      // not fused: join_kernel fills the movers' entries
     }
-    new_id[id] = out;
+    if (id0 + 3u < num_blocks) {
+      const i32x4 v = {out[0], out[1], out[2], out[3]};
+      *(i32x4*)(new_id + id0) = v;
+    } else {
+      for (uint32_t e = 0; e < 4u && id0 + e < num_blocks; ++e) new_id[id0 + e] = out[e];
+    }
+  }
+  if (!FUSED) return;
+
+  // Fused shape: the whole dst list was written by this workgroup; after the
+  // barrier every mover reads its destination by rank (neighbouring lanes read
+  // neighbouring entries) and the groups that hold movers are stored again.
+  __syncthreads();
+  for (uint32_t it = first_pass_at_boundary; it < 16u; ++it) {
+    const uint32_t local = (it * kPlanThreads + tid) * 4u;
+    const uint32_t id0 = group_first_id + local;
+    if (id0 >= num_blocks) break;
+    const uint32_t wl = local >> 6, bit0 = local & 63u;
+    const uint64_t movers = s_live[wl] & ~low_mask(id0 - bit0, boundary);
+    if (((movers >> bit0) & 0xFull) == 0) continue;
+    uint32_t m_rank = (uint32_t)(s_rank[wl] >> 32) + (uint32_t)__popcll(movers & ((1ull << bit0) - 1ull));
+#pragma unroll
+    for (uint32_t e = 0; e < 4u; ++e)
+      if ((movers >> (bit0 + e)) & 1ull) new_id[id0 + e] = dst[m_rank++];
   }
 }
 

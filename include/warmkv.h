@@ -287,6 +287,75 @@ int kv_vmm_restore(kv_vmm_pool* pool);
 /* Unmap everything, release the physical memory and both ranges. */
 int kv_vmm_pool_destroy(kv_vmm_pool* pool);
 
+/* ------------------------------------------------------------------------
+ * Control-plane formulas of the paper (host arithmetic in double precision;
+ * no device work).  They decide what the path above is asked to do: which
+ * model to prewarm where.
+ * ------------------------------------------------------------------------ */
+
+/* Corrective seasonal predictor, Sec. 3.1, Eq. 1-3.  history [host] is
+ * loads[n_days][n_windows], row-major, day 0 the oldest; the call predicts the
+ * load of window `window` on day `day` from the D previous days (all windows)
+ * and the windows of day `day` before `window`:
+ *   P(k,i)     = (1/D) * sum_{d=1..D} L(k-d, i)
+ *   Delta(k,i) = sum_{w=1..m} (L(k,i-w) - P(k,i-w)) * 2^(w-1) / (2^m - 1),  m = min(i, N)
+ *   prediction = P(k,i) + Delta(k,i);   Delta = 0 when i = 0.
+ * Requires D >= 1, day >= D, day < n_days, window < n_windows, N <= 62
+ * (else KV_E_RANGE).  The paper's settings are D = 7, N = 10. */
+int ws_predict_load(const double* history, uint32_t n_days, uint32_t n_windows,
+                    uint32_t day, uint32_t window, uint32_t D, uint32_t N, double* prediction);
+
+/* One served model, inputs of the prewarming score and of the placement. */
+typedef struct ws_model {
+  double   size_bytes;     /* S: bytes of weights of one replica                         */
+  double   load_avg;       /* L_A: predicted average load of the next window            */
+  double   load_peak;      /* L_P: predicted peak load                                   */
+  double   cold_latency;   /* T_c: time to load the whole model from scratch            */
+  uint32_t degree;         /* D: GPUs per replica, >= 1                                  */
+  uint32_t batch;          /* B: maximum batch size, >= 1                                */
+  uint32_t active;         /* K: instances serving now                                   */
+  uint32_t reserved;
+} ws_model;
+
+/* Replicas to prewarm for one model and their scores, App. B.1:
+ *   N_basic = max(ceil(L_A/B) - K, 0),  N_burst = max(ceil(L_P/B) - N_basic - K, 0)
+ *   S_basic(i) = exp(-i/(N_basic+N_burst)) * T_c
+ *   S_burst(i) = exp(-(N_basic+i)/(N_basic+N_burst)) * T_c * (L_P - L_A)/L_A
+ * scores [host, capacity entries] receives the basic scores, then the burst
+ * scores (a burst score is +infinity when L_A == 0).  Returns KV_E_TOOBIG if
+ * capacity < N_basic + N_burst (the counts are still written), KV_E_RANGE for
+ * negative loads, B == 0, degree == 0 or more than 10^6 replicas. */
+int ws_replica_scores(const ws_model* model, uint32_t* n_basic, uint32_t* n_burst,
+                      double* scores, uint32_t capacity);
+
+/* One placement decision: replica `replica` (0-based; basic ones first) of
+ * model `model` goes to GPUs [first_gpu, first_gpu + degree). */
+typedef struct ws_placement {
+  uint32_t model;
+  uint32_t replica;
+  uint32_t first_gpu;
+  uint32_t is_burst;
+  double   score;
+} ws_placement;
+
+/* Prewarming model placement, Sec. 3.2 Alg. 1 and App. B.2.  Replicas of all
+ * models are ordered basic before burst, then by score descending (ties: lower
+ * model index, then lower replica index).  Candidate groups for a replica of
+ * degree D are the aligned runs of D GPUs inside one server
+ * (gpus_per_server % D == 0 required), every GPU with at least ceil(S/D) free
+ * bytes; aligned runs make any two placements disjoint or nested, never
+ * partially overlapping.  For each group, H and R are the highest and the sum
+ * of the scores of replicas already placed on any of its GPUs (H = -infinity,
+ * R = 0 for an untouched group).  If some group has H < score, the one with
+ * the least R among those is taken, else the one with the least R overall
+ * (ties: lowest first_gpu); its GPUs lose ceil(S/D) free bytes.  A replica with
+ * no candidate group is skipped.
+ * out [host, capacity] receives the decisions in placement order and *n_out
+ * their number; gpu_free_bytes [host, n_gpus] is updated only on KV_OK. */
+int ws_place_replicas(const ws_model* models, uint32_t n_models,
+                      double* gpu_free_bytes, uint32_t n_gpus, uint32_t gpus_per_server,
+                      ws_placement* out, uint32_t capacity, uint32_t* n_out);
+
 /* Library version, "major.minor". */
 const char* warmkv_version(void);
 

@@ -32,7 +32,8 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
            "weights_materialize_pipelined", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
-           "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "warmkv_version")
+           "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
+           "ws_place_replicas", "warmkv_version")
 
 
 class WarmKVError(RuntimeError):
@@ -68,6 +69,17 @@ class wm_tensor(Structure):
 class wm_piece(Structure):
     _fields_ = [("tensor", c_uint32), ("early", c_uint32), ("src_offset", c_uint64), ("dst_offset", c_uint64),
                 ("bytes", c_uint64)]
+
+
+class ws_model(Structure):
+    _fields_ = [("size_bytes", ctypes.c_double), ("load_avg", ctypes.c_double), ("load_peak", ctypes.c_double),
+                ("cold_latency", ctypes.c_double), ("degree", c_uint32), ("batch", c_uint32), ("active", c_uint32),
+                ("reserved", c_uint32)]
+
+
+class ws_placement(Structure):
+    _fields_ = [("model", c_uint32), ("replica", c_uint32), ("first_gpu", c_uint32), ("is_burst", c_uint32),
+                ("score", ctypes.c_double)]
 
 
 _lib = None
@@ -123,6 +135,14 @@ def load():
     L.kv_vmm_restore.argtypes = [c_void_p]
     L.kv_vmm_pool_destroy.restype = c_int
     L.kv_vmm_pool_destroy.argtypes = [c_void_p]
+    L.ws_predict_load.restype = c_int
+    L.ws_predict_load.argtypes = [c_void_p, c_uint32, c_uint32, c_uint32, c_uint32, c_uint32, c_uint32,
+                                  POINTER(ctypes.c_double)]
+    L.ws_replica_scores.restype = c_int
+    L.ws_replica_scores.argtypes = [POINTER(ws_model), POINTER(c_uint32), POINTER(c_uint32), c_void_p, c_uint32]
+    L.ws_place_replicas.restype = c_int
+    L.ws_place_replicas.argtypes = [POINTER(ws_model), c_uint32, c_void_p, c_uint32, c_uint32, POINTER(ws_placement),
+                                    c_uint32, POINTER(c_uint32)]
     L.warmkv_version.restype = c_char_p
     L.warmkv_version.argtypes = []
     _lib = L
@@ -272,6 +292,47 @@ def kv_vmm_restore(pool: int) -> None:
 
 def kv_vmm_pool_destroy(pool: int) -> None:
     _check("kv_vmm_pool_destroy", load().kv_vmm_pool_destroy(pool))
+
+
+def ws_predict_load(history, day: int, window: int, D: int = 7, N: int = 10) -> float:
+    """history: C-contiguous float64 numpy array [n_days][n_windows] (day 0 the oldest)."""
+    out = ctypes.c_double()
+    _check("ws_predict_load", load().ws_predict_load(history.ctypes.data, history.shape[0], history.shape[1], day,
+                                                     window, D, N, byref(out)))
+    return out.value
+
+
+def make_model(size_bytes, load_avg, load_peak, cold_latency, degree, batch, active) -> ws_model:
+    return ws_model(size_bytes, load_avg, load_peak, cold_latency, degree, batch, active, 0)
+
+
+def ws_replica_scores(model: ws_model):
+    """Returns (n_basic, n_burst, [scores])."""
+    nb, nu = c_uint32(), c_uint32()
+    rc = load().ws_replica_scores(byref(model), byref(nb), byref(nu), None, 0)
+    if rc not in (KV_OK, KV_E_TOOBIG):
+        raise WarmKVError("ws_replica_scores", rc)
+    n = nb.value + nu.value
+    buf = (ctypes.c_double * max(1, n))()
+    _check("ws_replica_scores", load().ws_replica_scores(byref(model), byref(nb), byref(nu), buf, n))
+    return nb.value, nu.value, list(buf[:n])
+
+
+def ws_place_replicas(models, gpu_free_bytes, gpus_per_server: int):
+    """models: list of ws_model; gpu_free_bytes: float64 numpy array, updated in place.
+    Returns [(model, replica, first_gpu, is_burst, score)] in placement order."""
+    arr = (ws_model * max(1, len(models)))(*models)
+    count = c_uint32()
+    cap = 64
+    while True:
+        out = (ws_placement * cap)()
+        rc = load().ws_place_replicas(arr, len(models), gpu_free_bytes.ctypes.data, gpu_free_bytes.size,
+                                      gpus_per_server, out, cap, byref(count))
+        if rc == KV_E_TOOBIG and count.value > cap:
+            cap = count.value
+            continue
+        _check("ws_place_replicas", rc)
+        return [(p.model, p.replica, p.first_gpu, p.is_burst, p.score) for p in out[:count.value]]
 
 
 def warmkv_version() -> str:

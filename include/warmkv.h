@@ -109,8 +109,8 @@ size_t kv_plan_workspace_bytes(uint32_t num_blocks, uint32_t boundary);
 int kv_plan_bind(kv_plan* plan, void* workspace, size_t workspace_bytes,
                  uint32_t num_blocks, uint32_t boundary);
 
-/* Relocation planner ("which physical blocks are unused, and where does each
- * block that is in the way go": App. C, Fig. 4b step 1; how much to reclaim is
+/* Relocation planner: which physical blocks are unused, and where each block
+ * that is in the way goes (App. C, Fig. 4b step 1; how much to reclaim is
  * Eq. 4's business and arrives as `boundary`).
  * live_in [device]: uint64[ceil(NB/64)], bit (i%64) of word (i/64) set <=> block
  * i holds live KV; bits at or beyond NB in the last word are ignored.  Must
@@ -169,9 +169,9 @@ typedef struct wm_tensor {
   uint64_t    dst_offset;
 } wm_tensor;
 
-/* Weight materialisation ("the model's weights are then loaded into these
- * pages", App. C, Fig. 4b step 3; host memory to GPU over the host link,
- * Sec. 4.1; a copy is issued as soon as its destination is ready, App. C).
+/* Weight materialisation: the new model's weights go into the space that
+ * unused KV blocks gave up (App. C, Fig. 4b step 3), from host memory over the
+ * host link (Sec. 4.1), each copy issued once its destination is ready (App. C).
  * The reclaimed region is bytes [boundary*block_bytes, num_blocks*block_bytes)
  * of the pool.  In a layer-major pool it is the L strips taken one after the
  * other in layer order (strip l = region offsets [l*S, (l+1)*S), S =
@@ -198,8 +198,7 @@ typedef struct wm_piece {
 } wm_piece;
 
 /* Block-granular pipelining of the weight stream (the paper pipelines page
- * mapping and copying: "as soon as a page is mapped, its copy is issued",
- * App. C).  A block of the reclaimed region that was free when the plan was
+ * mapping and weight copying page by page, App. C).  A block of the reclaimed region that was free when the plan was
  * made is ready at once; one that holds a moving block is ready only after
  * kv_compact has read it.  live_host [host] is the bitmap kv_plan_reclaim was
  * given (before the move).  Tensors are walked in the caller's order and cut
@@ -233,9 +232,8 @@ int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
 int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks,
                           uint32_t running, uint32_t max_batch);
 
-/* Reverse switch: the reserve proved too small, so prewarmed weights give
- * space back ("when the reserved KV cache space becomes insufficient to serve
- * existing requests, we evict prewarmed weights", Sec. 3.3).  The boundary
+/* Reverse switch: the reserve proved too small, so prewarmed weights are
+ * evicted and give their space back to the KV cache (Sec. 3.3, end).  The boundary
  * rises from old_boundary to new_boundary (old <= new <= num_blocks); blocks
  * [old, new) return to the KV allocator as free ids (no block is live there,
  * so no bitmap bit changes and no byte moves).  For every tensor placed by

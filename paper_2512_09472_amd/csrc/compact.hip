@@ -1,8 +1,8 @@
 // Block copy of the KV reclaim: for k < n_moves, block dst[k] <- block src[k].
 // This is the bandwidth-bound step (2 * n_moves * block_bytes of HBM traffic);
-// the rest of the path is microseconds.  It stands in for the paper's
-// "map the physical pages of unused KV blocks to the new model's slot"
-// (App. C, Fig. 4b step 2): here the unused space is made contiguous instead.
+// the rest of the path is microseconds.  It stands in for the paper's step of
+// mapping the pages under unused KV blocks into the new model's slot (App. C,
+// Fig. 4b step 2): here the unused space is made contiguous instead.
 //
 // Shape.  The work list is (move, chunk) units of 64 KiB in list order (in a
 // layer-major pool a move is one tile per layer slab: (move, layer, chunk)).  One

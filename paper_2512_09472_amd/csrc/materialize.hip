@@ -7,8 +7,9 @@
 // The reclaimed range still holds moving blocks until kv_compact has read
 // them.  The plain entry point therefore waits on the caller's compaction
 // event before the first request.  The pipelined one follows the paper's rule
-// "copy as soon as the destination is ready" at block granularity: bytes that
-// land in blocks that were free when the plan was made go out before the wait.
+// (a copy starts once its destination is ready, App. C) at block granularity:
+// bytes that land in blocks that were free when the plan was made go out
+// before the wait.
 #include <algorithm>
 #include <vector>
 

@@ -6,20 +6,22 @@
 //
 // Shape.  The work list is (move, chunk) units of 64 KiB in list order (in a
 // layer-major pool a move is one tile per layer slab: (move, layer, chunk)).  One
-// workgroup per compute unit stays resident and draws units from a single
-// device-wide ticket counter, so at any moment the 256 workgroups stream one
-// narrow, advancing window (about 16 MiB of sources and as much of
+// 256-lane workgroup per compute unit stays resident and draws units from a
+// single device-wide ticket counter, so at any moment the 256 workgroups stream
+// one narrow, advancing window (about 16 MiB of sources and as much of
 // destinations).  Measured on MI355X this ordering is what matters: a static
 // grid-stride assignment lets workgroups drift apart, the window smears over
-// hundreds of MiB, and the same loads and stores run about 25 % slower.  The
-// ticket for the next unit is drawn before the current unit is copied, which
-// hides the atomic's latency; 64 KiB per ticket keeps the counter well below
-// the rate one address sustains.  The grid never depends on n_moves, which
+// hundreds of MiB, and the same loads and stores run about 25 % slower.  More
+// workgroups or bigger units widen the window and lose; 32 KiB units hit the
+// rate one counter address sustains.  The grid never depends on n_moves, which
 // lives in device memory (no host sync after the planner).
 //
-// Each lane issues UNROLL independent 128-bit loads before its first store; a
-// wavefront covers 1 KiB per instruction, fully coalesced.  Accesses are
-// non-temporal: gigabytes stream through once and should not evict anything.
+// Inside a unit every lane issues all 16 of its 128-bit loads (the whole
+// 64 KiB, 1 KiB per wavefront instruction, fully coalesced) before its first
+// store: long read bursts followed by long write bursts measured 5 % faster
+// than interleaving 32 KiB at a time.  Lane 0 draws the ticket and resolves it
+// to addresses; the other lanes take them from LDS.  Accesses are non-temporal:
+// gigabytes stream through once and should not evict anything.
 // Sources lie at or above the boundary and destinations below it, so no two
 // moves overlap and any order is correct; the kernel checks that property per
 // move instead of staging through LDS.
@@ -32,6 +34,7 @@ constexpr uint32_t kCopyThreads = 256;
 constexpr uint32_t kVecBytes = 16;
 constexpr uint32_t kRowBytes = kCopyThreads * kVecBytes;  // 4 KiB per workgroup per instruction
 constexpr uint32_t kDefaultChunk = 65536;
+constexpr uint32_t kDefaultUnroll = 16;                   // 16 rows = one whole 64 KiB unit per step
 
 template <bool NT>
 __device__ __forceinline__ u32x4 load16(const u32x4* p) {
@@ -62,10 +65,23 @@ struct CopyArgs {
   uint32_t seg_outer;       // unit order: 1 = segment-major (layer by layer), 0 = move-major
 };
 
-// Copy unit u = (move k, segment g, chunk c).  u is wavefront-uniform.
-template <int UNROLL, bool NT>
-__device__ __forceinline__ void copy_unit(const CopyArgs& a, uint32_t n_moves, uint32_t u, uint32_t tid) {
-  constexpr uint32_t kStep = kRowBytes * UNROLL;  // bytes per workgroup per inner iteration
+// One unit of work, resolved: where to read, where to write, how much.
+struct Unit {
+  uint32_t ticket;
+  uint32_t len;  // 0: nothing to copy (a move that failed the src >= boundary > dst check)
+  uint64_t src_off;
+  uint64_t dst_off;
+};
+
+// Lane 0 only: draw the next ticket from the device-wide counter and resolve
+// it to (move k, segment g, chunk c) and on to byte offsets.
+__device__ __forceinline__ Unit draw_unit(const CopyArgs& a, uint32_t n_moves, uint32_t n_units) {
+  Unit unit;
+  unit.ticket = atomicAdd(&a.state->ticket, 1u);
+  unit.len = 0;
+  unit.src_off = unit.dst_off = 0;
+  if (unit.ticket >= n_units) return unit;
+  const uint32_t u = unit.ticket;
   uint32_t k, g, c;
   if (a.seg_outer) {  // all moves of segment (layer) 0, then of segment 1, ...
     const uint32_t per_seg = n_moves * a.chunks_per_seg;
@@ -81,17 +97,33 @@ __device__ __forceinline__ void copy_unit(const CopyArgs& a, uint32_t n_moves, u
   }
   const uint32_t s = (uint32_t)a.src[k], d = (uint32_t)a.dst[k];
   if (s < a.boundary || s >= a.num_blocks || d >= a.boundary) {  // never true for a planner-made plan
-    if (tid == 0) atomicExch(&a.state->status, KV_E_BADPLAN);
-    return;
+    atomicExch(&a.state->status, KV_E_BADPLAN);
+    return unit;
   }
   const uint64_t off = (uint64_t)g * a.seg_stride + (uint64_t)c * a.chunk_bytes;
   const uint64_t left = a.seg_bytes - (uint64_t)c * a.chunk_bytes;
-  const uint32_t len = left < a.chunk_bytes ? (uint32_t)left : a.chunk_bytes;
-  const u32x4* __restrict__ sp = (const u32x4*)(a.base + (uint64_t)s * a.block_stride + off);
-  u32x4* __restrict__ dp = (u32x4*)(a.base + (uint64_t)d * a.block_stride + off);
+  unit.len = left < a.chunk_bytes ? (uint32_t)left : a.chunk_bytes;
+  unit.src_off = (uint64_t)s * a.block_stride + off;
+  unit.dst_off = (uint64_t)d * a.block_stride + off;
+  return unit;
+}
 
+// readfirstlane returns a signed int: go through uint32_t so that a low half
+// with bit 31 set is not sign-extended into the high half.
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ uint64_t uniform64(uint64_t v) {
+  const uint32_t hi = uniform32((uint32_t)(v >> 32)), lo = uniform32((uint32_t)v);
+  return ((uint64_t)hi << 32) | (uint64_t)lo;
+}
+
+// Copy len bytes (multiple of 16).  Every step issues all of its loads before
+// its first store; with the default shape one step is the whole unit.
+template <int UNROLL, bool NT>
+__device__ __forceinline__ void copy_bytes(const u32x4* __restrict__ sp, u32x4* __restrict__ dp, uint32_t len,
+                                           uint32_t tid) {
+  constexpr uint32_t kStep = kRowBytes * UNROLL;
   uint32_t done = 0;
-  for (; done + kStep <= len; done += kStep) {  // full rows, no bounds checks
+  for (; done + kStep <= len; done += kStep) {  // full steps, no bounds checks
     u32x4 v[UNROLL];
     const uint32_t i = done / kVecBytes + tid;
 #pragma unroll
@@ -99,28 +131,46 @@ __device__ __forceinline__ void copy_unit(const CopyArgs& a, uint32_t n_moves, u
 #pragma unroll
     for (int j = 0; j < UNROLL; ++j) store16<NT>(dp + i + j * kCopyThreads, v[j]);
   }
-  const uint32_t n_vec = len / kVecBytes;  // ragged tail of the chunk
-  for (uint32_t i = done / kVecBytes + tid; i < n_vec; i += kCopyThreads) store16<NT>(dp + i, load16<NT>(sp + i));
+  if (done < len) {  // last, partial step: same shape, each row guarded
+    u32x4 v[UNROLL];
+    const uint32_t n_vec = len / kVecBytes;
+    const uint32_t i = done / kVecBytes + tid;
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j)
+      if (i + j * kCopyThreads < n_vec) v[j] = load16<NT>(sp + i + j * kCopyThreads);
+#pragma unroll
+    for (int j = 0; j < UNROLL; ++j)
+      if (i + j * kCopyThreads < n_vec) store16<NT>(dp + i + j * kCopyThreads, v[j]);
+  }
 }
 
-// Units in ticket order: one device-wide counter, next ticket drawn ahead.
-template <int UNROLL, bool NT>
+// Persistent workgroups; units are handed out in list order by one ticket
+// counter.  Lane 0 draws and resolves the next unit while (PREFETCH) or after
+// (!PREFETCH) the current one is copied; the others pick it up from LDS.
+template <int UNROLL, bool NT, bool PREFETCH>
 __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a) {
   // No early return: every workgroup must draw its one out-of-range ticket and
   // sign out below, or the counters would not return to zero.
   const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
   const uint32_t n_units = n_moves * a.units_per_move;  // host checked: fits 31 bits
   const uint32_t tid = threadIdx.x;
-  __shared__ uint32_t s_ticket[2];
-  if (tid == 0) s_ticket[0] = atomicAdd(&a.state->ticket, 1u);
+  __shared__ Unit s_unit[2];
+  if (tid == 0) s_unit[0] = draw_unit(a, n_moves, n_units);
   __syncthreads();
   uint32_t slot = 0;
   for (;;) {
-    const uint32_t u = __builtin_amdgcn_readfirstlane(s_ticket[slot]);
-    if (u >= n_units) break;
+    const uint32_t ticket = uniform32(s_unit[slot].ticket);
+    if (ticket >= n_units) break;
+    const uint32_t len = uniform32(s_unit[slot].len);
+    const uint64_t src_off = uniform64(s_unit[slot].src_off);
+    const uint64_t dst_off = uniform64(s_unit[slot].dst_off);
     // The other slot was last read before the previous barrier: free to refill.
-    if (tid == 0) s_ticket[slot ^ 1u] = atomicAdd(&a.state->ticket, 1u);
-    copy_unit<UNROLL, NT>(a, n_moves, u, tid);
+    if (PREFETCH && tid == 0) s_unit[slot ^ 1u] = draw_unit(a, n_moves, n_units);
+    copy_bytes<UNROLL, NT>((const u32x4*)(a.base + src_off), (u32x4*)(a.base + dst_off), len, tid);
+    if (!PREFETCH) {
+      __syncthreads();
+      if (tid == 0) s_unit[slot ^ 1u] = draw_unit(a, n_moves, n_units);
+    }
     __syncthreads();
     slot ^= 1u;
   }
@@ -135,21 +185,13 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
   }
 }
 
-// Units in static grid-stride order (kept for comparison; slower on MI355X).
-template <int UNROLL, bool NT>
-__global__ __launch_bounds__(kCopyThreads) void compact_static_kernel(CopyArgs a) {
-  if (a.state->status != KV_OK) return;
-  const uint32_t n_moves = a.state->n_moves;
-  const uint32_t n_units = n_moves * a.units_per_move;
-  for (uint32_t u = blockIdx.x; u < n_units; u += gridDim.x) copy_unit<UNROLL, NT>(a, n_moves, u, threadIdx.x);
-}
-
-template <int UNROLL, bool NT>
-int launch(const CopyArgs& a, uint32_t workgroups, bool tickets, hipStream_t s) {
-  if (tickets)
-    hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, NT>), dim3(workgroups), dim3(kCopyThreads), 0, s, a);
-  else
-    hipLaunchKernelGGL((compact_static_kernel<UNROLL, NT>), dim3(workgroups), dim3(kCopyThreads), 0, s, a);
+template <int UNROLL>
+int launch(const CopyArgs& a, uint32_t workgroups, bool nt, bool prefetch, hipStream_t s) {
+  const dim3 grid(workgroups), block(kCopyThreads);
+  if (nt && prefetch) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, true, true>), grid, block, 0, s, a);
+  else if (nt) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, true, false>), grid, block, 0, s, a);
+  else if (prefetch) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, false, true>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, false, false>), grid, block, 0, s, a);
   return launch_rc();
 }
 
@@ -172,10 +214,8 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
     flags = tuning->flags;
   }
   if ((chunk % kRowBytes) != 0 || workgroups > (1u << 20)) return KV_E_RANGE;
-  const uint32_t unroll_sel = (flags >> 4) & 0xFu;  // 0 = pick from the chunk size
-  const uint32_t unroll = unroll_sel ? unroll_sel
-                                     : (chunk >= 8 * kRowBytes ? 8u : (chunk >= 4 * kRowBytes ? 4u : (chunk >= 2 * kRowBytes ? 2u : 1u)));
-  if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return KV_E_RANGE;
+  const uint32_t unroll = (flags >> 4) & 0x3Fu ? (flags >> 4) & 0x3Fu : kDefaultUnroll;
+  if (unroll != 2 && unroll != 4 && unroll != 8 && unroll != 16 && unroll != 32) return KV_E_RANGE;
 
   const bool layer_major = pool->layer_stride_bytes != 0;
   if (layer_major && (pool->layer_stride_bytes % 256u != 0 ||
@@ -218,13 +258,14 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
   }
 
   const bool nt = (flags & 1u) == 0;
-  const bool tickets = (flags & 2u) == 0;
+  const bool prefetch = (flags & 2u) == 0;
   hipStream_t s = (hipStream_t)stream;
   switch (unroll) {
-    case 1: return nt ? launch<1, true>(a, workgroups, tickets, s) : launch<1, false>(a, workgroups, tickets, s);
-    case 2: return nt ? launch<2, true>(a, workgroups, tickets, s) : launch<2, false>(a, workgroups, tickets, s);
-    case 4: return nt ? launch<4, true>(a, workgroups, tickets, s) : launch<4, false>(a, workgroups, tickets, s);
-    default: return nt ? launch<8, true>(a, workgroups, tickets, s) : launch<8, false>(a, workgroups, tickets, s);
+    case 2: return launch<2>(a, workgroups, nt, prefetch, s);
+    case 4: return launch<4>(a, workgroups, nt, prefetch, s);
+    case 8: return launch<8>(a, workgroups, nt, prefetch, s);
+    case 16: return launch<16>(a, workgroups, nt, prefetch, s);
+    default: return launch<32>(a, workgroups, nt, prefetch, s);
   }
 }
 

@@ -123,6 +123,19 @@ def test_full_size_reclaim(oracle, index):
     torch.cuda.empty_cache()
 
 
+def test_byte_offsets_beyond_2_and_4_gib(oracle):
+    """A 4.5 GiB pool: source and destination byte offsets cross 2^31 and 2^32 (their low 32-bit
+    halves take every sign), which small pools never exercise."""
+    cfg = CONFIGS[1].scaled(num_blocks=2304, num_seqs=64)
+    run = FullRun(cfg, oracle)
+    assert int(run.p.src.max()) * cfg.block_bytes > (1 << 32) and int(run.p.dst.max()) * cfg.block_bytes > (1 << 31)
+    run.check_plan_and_tables()
+    run.check_pool()
+    run.check_sampled_blocks(n_each=3)
+    del run
+    torch.cuda.empty_cache()
+
+
 def test_full_size_layer_major_reclaim(oracle):
     """The 8B-shaped pool kept layer-major (32 slabs of 1.25 GiB): every slab is checked in full
     against the oracle's plan, slab by slab, with the device generator."""

@@ -48,13 +48,13 @@ SCALED = {
     "cfg5_tiny_tile": CONFIGS[4].scaled(num_blocks=2048, num_layers=1, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512),
 }
 
-TUNINGS = [None,                                                        # defaults: tickets, 64 KiB, one WG per CU
-           dict(chunk_bytes=4096, flags=1 << 4),
+TUNINGS = [None,                                                        # defaults: 64 KiB units, 16 loads per lane, one WG per CU
+           dict(chunk_bytes=4096, flags=2 << 4),                        # units smaller than one step
            dict(chunk_bytes=65536, flags=(8 << 4) | 1),                 # cached accesses
            dict(workgroups=7, chunk_bytes=8192, flags=2 << 4),
            dict(workgroups=3000, chunk_bytes=32768, flags=4 << 4),      # more workgroups than fit at once
-           dict(workgroups=5000, chunk_bytes=32768, flags=(4 << 4) | 2),   # static grid-stride order
-           dict(workgroups=256, chunk_bytes=1 << 20, flags=(2 << 4) | 2)]
+           dict(workgroups=5000, chunk_bytes=32768, flags=(4 << 4) | 2),   # next ticket drawn after the copy
+           dict(workgroups=256, chunk_bytes=1 << 20, flags=(32 << 4) | 2)]
 
 
 @pytest.mark.parametrize("name", list(SCALED))
@@ -430,7 +430,7 @@ def test_layer_major_reclaim_matches_oracle(oracle, name):
         hosts.append(h)
     assert oracle.materialize_strips(want, cfg.tile_bytes, cfg.num_layers, cfg.num_blocks, cfg.boundary, stride,
                                      [(h.numpy(), o) for h, o in zip(hosts, offs)]) == 0
-    for tuning in (None, dict(chunk_bytes=4096, flags=1 << 4), dict(workgroups=3000, chunk_bytes=16384, flags=4 << 4),
+    for tuning in (None, dict(chunk_bytes=4096, flags=2 << 4), dict(workgroups=3000, chunk_bytes=16384, flags=4 << 4),
                    dict(workgroups=512, chunk_bytes=32768, flags=(2 << 4) | 2), dict(flags=4),
                    dict(workgroups=100, chunk_bytes=8192, flags=(2 << 4) | 2 | 4)):
         _say(f"[layer-major] {name} tile={cfg.tile_bytes} L={cfg.num_layers} NB={cfg.num_blocks} pad={pad} tuning={tuning}")

@@ -138,7 +138,7 @@ typedef struct kv_compact_tuning {
   uint32_t workgroups;     /* persistent grid size (default: one per compute unit)       */
   uint32_t chunk_bytes;    /* bytes per work ticket; multiple of 4096 (default 65536)    */
   uint32_t flags;          /* bit 0: plain (cached) instead of non-temporal accesses;
-                              bit 1: draw the next ticket after the copy, not during it;
+                              bit 1: draw the next ticket during the copy, not after it;
                               bit 2: layer-major pools: move by move instead of slab by slab;
                               bits 4-9: 128-bit loads in flight per lane: 2, 4, 8, 16 (default)
                                         or 32                                              */

@@ -53,7 +53,7 @@ TUNINGS = [None,                                                        # defaul
            dict(chunk_bytes=65536, flags=(8 << 4) | 1),                 # cached accesses
            dict(workgroups=7, chunk_bytes=8192, flags=2 << 4),
            dict(workgroups=3000, chunk_bytes=32768, flags=4 << 4),      # more workgroups than fit at once
-           dict(workgroups=5000, chunk_bytes=32768, flags=(4 << 4) | 2),   # next ticket drawn after the copy
+           dict(workgroups=5000, chunk_bytes=32768, flags=(4 << 4) | 2),   # next ticket drawn during the copy
            dict(workgroups=256, chunk_bytes=1 << 20, flags=(32 << 4) | 2)]
 
 

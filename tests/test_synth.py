@@ -95,3 +95,29 @@ def test_normal_table_and_content():
     assert not np.array_equal(a, item_bytes_host(6, 3, 4096, t))
     raw = item_bytes_host(5, 3, 4096, None)
     assert abs(float(raw.mean()) - 127.5) < 8
+
+
+def test_bench_threaded_host_copy_equals_the_oracle(oracle):
+    """The bench-only all-cores host copy does the same moves as the oracle's block copy."""
+    import ctypes
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    so = os.path.join(root, "bench_hostcopy.so")
+    subprocess.run(["g++", "-O2", "-std=c++17", "-pthread", "-fPIC", "-shared",
+                    os.path.join(root, "bench_hostcopy.cpp"), "-o", so], check=True)
+    lib = ctypes.CDLL(so)
+    lib.hostcopy_moves.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p,
+                                   ctypes.c_uint32, ctypes.c_uint32]
+    lib.hostcopy_moves.restype = None
+    cfg = CONFIGS[4].scaled(num_blocks=512, num_layers=1, block_size=1, kv_heads=1, head_dim=64, len_hi=16, num_seqs=128)
+    w = make_workload(cfg)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    pool = np.random.default_rng(0).integers(0, 256, cfg.pool_bytes, dtype=np.uint8)
+    want = pool.copy()
+    oracle.compact(want, cfg.block_bytes, p)
+    for threads in (1, 3, 8, 1000):
+        got = pool.copy()
+        src, dst = np.ascontiguousarray(p.src), np.ascontiguousarray(p.dst)
+        lib.hostcopy_moves(got.ctypes.data, cfg.block_bytes, src.ctypes.data, dst.ctypes.data, p.n_moves, threads)
+        assert np.array_equal(got, want), threads

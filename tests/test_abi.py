@@ -231,3 +231,10 @@ def test_product_path_never_touches_the_oracle():
         assert "oracle" not in open(os.path.join(ROOT, "include", f)).read().lower()
     src = open(os.path.join(ROOT, "oracle", "warmkv_oracle.cpp")).read() + open(os.path.join(ROOT, "oracle", "__init__.py")).read()
     assert "warmkv.h" not in src and "paper_2512_09472_amd" not in src and "import synth" not in src
+
+
+def test_header_is_valid_c99_and_cxx():
+    import subprocess
+    h = os.path.join(ROOT, "include", "warmkv.h")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", h], check=True)
+    subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++", h], check=True)

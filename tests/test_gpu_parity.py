@@ -46,6 +46,8 @@ SCALED = {
     "cfg4_odd_boundary": CONFIGS[3].scaled(num_blocks=1536, num_layers=4, num_seqs=128),
     "cfg5_frag": CONFIGS[4].scaled(num_blocks=4096, num_layers=2, num_seqs=1024),
     "cfg5_tiny_tile": CONFIGS[4].scaled(num_blocks=2048, num_layers=1, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512),
+    # more than 65 536 blocks: the planner's several-workgroup shape plus its join kernel feed the copy
+    "many_small_blocks": CONFIGS[4].scaled(num_blocks=150_000, num_layers=2, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=6000),
 }
 
 TUNINGS = [None,                                                        # defaults: 64 KiB units, 16 loads per lane, one WG per CU

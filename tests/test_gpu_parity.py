@@ -553,3 +553,19 @@ def test_reclaim_step_replays_from_a_hip_graph(oracle):
         assert st.ticket == 0 and st.finished == 0 and st.n_bad_entries == 0
         assert np.array_equal(tables_dev.cpu().numpy(), want_tables), f"replay {replay}"
         assert np.array_equal(pool_dev.cpu().numpy(), want_pool), f"replay {replay}"
+
+
+def test_plain_c_client_of_the_abi(tmp_path):
+    """tests/c_abi_demo.c: a C99 program (no Python, no C++) drives plan, compact, materialize and
+    remap through the shared library and checks the result on the host itself."""
+    import os
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    exe = str(tmp_path / "c_abi_demo")
+    libdir = os.path.join(root, "paper_2512_09472_amd")
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-O1", "-I", os.path.join(root, "include"),
+                    "-I", "/opt/rocm/include", os.path.join(root, "tests", "c_abi_demo.c"), "-L", libdir, "-lwarmkv",
+                    "-L", "/opt/rocm/lib", "-lamdhip64", "-Wl,-rpath,/opt/rocm/lib", f"-Wl,-rpath,{libdir}",
+                    "-o", exe], check=True)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "c_abi_demo ok" in r.stdout, (r.returncode, r.stdout, r.stderr[-500:])

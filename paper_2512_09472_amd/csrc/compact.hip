@@ -20,8 +20,9 @@
 // 64 KiB, 1 KiB per wavefront instruction, fully coalesced) before its first
 // store: long read bursts followed by long write bursts measured 5 % faster
 // than interleaving 32 KiB at a time.  Lane 0 draws the ticket and resolves it
-// to addresses between two units; the other lanes take them from LDS.  Accesses are non-temporal:
-// gigabytes stream through once and should not evict anything.
+// to addresses between two units; the other lanes take them from LDS.
+// Accesses are non-temporal: gigabytes stream through once and should not
+// evict anything.
 // Sources lie at or above the boundary and destinations below it, so no two
 // moves overlap and any order is correct; the kernel checks that property per
 // move instead of staging through LDS.

@@ -10,8 +10,6 @@ namespace warmkv {
 
 constexpr int kWave = 64;                       // CDNA wavefront width
 constexpr uint32_t kMaxBlocks = 1u << 24;       // planner's supported pool size (blocks)
-constexpr uint32_t kPlanThreads = 1024;         // one bitmap word per thread, 16 waves
-constexpr uint32_t kIdsPerPlanGroup = kPlanThreads * 64;
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));

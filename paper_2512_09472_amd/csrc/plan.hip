@@ -5,13 +5,13 @@
 // paper App. C, Fig. 4b step 1; b itself comes from Sec. 3.3, Eq. 4.)
 //
 // Shape: one bitmap word per thread, 1024 threads (16 wavefronts) per
-// workgroup, so one workgroup covers 65 536 blocks.  Ranks come from a popcount
-// per word, a 64-lane shuffle scan, and a 16-entry cross-wave prefix in LDS;
-// movers and free ids are ranked in one pass by packing both counts into one
-// 64-bit scan value.  Pools above 65 536 blocks use several workgroups; each
-// gets its carry by reducing the words in front of it (a few KiB from L2)
-// instead of talking to its neighbours, and a tiny second kernel joins the two
-// lists into new_id.  With one workgroup everything is fused in one launch.
+// workgroup.  Ranks come from a popcount per word, a 64-lane shuffle scan, and
+// a cross-wave prefix in LDS; movers and free ids are ranked in one pass by
+// packing both counts into one 64-bit scan value.  Small pools (up to 32 768
+// blocks) are done by one workgroup, fused in one launch.  Larger ones use
+// several workgroups (256 or 1024 words each); each gets its carry by reducing
+// the words in front of it (a few KiB from L2) instead of talking to its
+// neighbours, and a tiny second kernel joins the two lists into new_id.
 // All outputs are produced in id order (ranks are monotone in ids), so even
 // the two lists are written nearly coalesced: a one-workgroup kernel lives on
 // one compute unit, and per-lane bit walks with strided stores cost it 3x.
@@ -84,21 +84,21 @@ __device__ __forceinline__ uint64_t lowest_set_bits(uint64_t m, uint32_t count) 
   return m & ((1ull << pos) - 1ull);
 }
 
-template <bool FUSED>
-__global__ __launch_bounds__(kPlanThreads) void plan_kernel(
+template <int THREADS, bool FUSED>
+__global__ __launch_bounds__(THREADS) void plan_kernel(
     const uint64_t* __restrict__ live_in, uint32_t n_words, uint32_t num_blocks, uint32_t boundary,
     int32_t* __restrict__ src, int32_t* __restrict__ dst, int32_t* __restrict__ new_id,
     uint64_t* __restrict__ live_out, kv_plan_state* __restrict__ state) {
-  constexpr int kWaves = kPlanThreads / kWave;
+  constexpr int kWaves = THREADS / kWave;
   __shared__ uint64_t s_wave[kWaves];
   __shared__ uint64_t s_carry[2][kWaves];
-  __shared__ uint64_t s_live[kPlanThreads];
-  __shared__ uint64_t s_rank[kPlanThreads];
+  __shared__ uint64_t s_live[THREADS];
+  __shared__ uint64_t s_rank[THREADS];
 
   const uint32_t tid = threadIdx.x;
   const uint32_t lane = tid & (kWave - 1);
   const uint32_t wave = tid / kWave;
-  const uint32_t first_word = blockIdx.x * kPlanThreads;
+  const uint32_t first_word = blockIdx.x * THREADS;
   const uint32_t wi = first_word + tid;
 
   const uint64_t word = wi < n_words ? live_in[wi] : 0ull;
@@ -113,7 +113,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
   uint64_t before = 0, total = 0;
   if (!FUSED) {
     uint64_t acc_before = 0, acc_all = 0;
-    for (uint32_t i = tid; i < n_words; i += kPlanThreads) {
+    for (uint32_t i = tid; i < n_words; i += THREADS) {
       const uint64_t c = pack_counts(classify(live_in[i], i, num_blocks, boundary));
       acc_all += c;
       if (i < first_word) acc_before += c;
@@ -176,9 +176,9 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
   __syncthreads();
 
   const uint32_t group_first_id = first_word * 64u;
-  const uint32_t first_pass_at_boundary = boundary > group_first_id ? (boundary - group_first_id) / (kPlanThreads * 4u) : 0u;
+  const uint32_t first_pass_at_boundary = boundary > group_first_id ? (boundary - group_first_id) / (THREADS * 4u) : 0u;
   for (uint32_t it = 0; it < 16u; ++it) {
-    const uint32_t local = (it * kPlanThreads + tid) * 4u;
+    const uint32_t local = (it * THREADS + tid) * 4u;
     const uint32_t id0 = group_first_id + local;
     if (id0 >= num_blocks) break;
     const uint32_t wl = local >> 6, bit0 = local & 63u;
@@ -219,7 +219,7 @@ __global__ __launch_bounds__(kPlanThreads) void plan_kernel(
   // neighbouring entries) and the groups that hold movers are stored again.
   __syncthreads();
   for (uint32_t it = first_pass_at_boundary; it < 16u; ++it) {
-    const uint32_t local = (it * kPlanThreads + tid) * 4u;
+    const uint32_t local = (it * THREADS + tid) * 4u;
     const uint32_t id0 = group_first_id + local;
     if (id0 >= num_blocks) break;
     const uint32_t wl = local >> 6, bit0 = local & 63u;
@@ -262,14 +262,25 @@ extern "C" int kv_plan_reclaim(const uint64_t* live_in, const kv_plan* plan, voi
   if (n_words != 0 && a0 < o1 && o0 < a1) return KV_E_OVERLAP;
 
   hipStream_t s = (hipStream_t)stream;
-  const uint32_t groups = n_words == 0 ? 1u : (n_words + kPlanThreads - 1) / kPlanThreads;
-  if (groups == 1) {
-    hipLaunchKernelGGL(plan_kernel<true>, dim3(1), dim3(kPlanThreads), 0, s, live_in, n_words, nb, b,
-                       plan->src, plan->dst, plan->new_id, plan->live_out, plan->state);
+  // Shape, from measurement: up to 32 768 blocks one 1024-lane workgroup does everything in one
+  // launch (12 us at 20 480 blocks).  Above that the bitmap is split into groups that run on
+  // different compute units, 256 words each up to 2^20 blocks (18 us at 65 536 blocks, against
+  // 27 us fused) and 1024 words beyond (fewer groups, each of which reduces all words in front of
+  // it), followed by the join kernel.
+  if (n_words <= 512) {
+    hipLaunchKernelGGL((plan_kernel<1024, true>), dim3(1), dim3(1024), 0, s, live_in, n_words, nb, b, plan->src,
+                       plan->dst, plan->new_id, plan->live_out, plan->state);
     return launch_rc();
   }
-  hipLaunchKernelGGL(plan_kernel<false>, dim3(groups), dim3(kPlanThreads), 0, s, live_in, n_words, nb, b,
-                     plan->src, plan->dst, plan->new_id, plan->live_out, plan->state);
+  if (nb <= (1u << 20)) {
+    const uint32_t groups = (n_words + 255u) / 256u;
+    hipLaunchKernelGGL((plan_kernel<256, false>), dim3(groups), dim3(256), 0, s, live_in, n_words, nb, b, plan->src,
+                       plan->dst, plan->new_id, plan->live_out, plan->state);
+  } else {
+    const uint32_t groups = (n_words + 1023u) / 1024u;
+    hipLaunchKernelGGL((plan_kernel<1024, false>), dim3(groups), dim3(1024), 0, s, live_in, n_words, nb, b,
+                       plan->src, plan->dst, plan->new_id, plan->live_out, plan->state);
+  }
   int rc = launch_rc();
   if (rc != KV_OK) return rc;
   uint32_t join_groups = (plan->capacity + 255u) / 256u;

@@ -569,3 +569,50 @@ def test_plain_c_client_of_the_abi(tmp_path):
                     "-o", exe], check=True)
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "c_abi_demo ok" in r.stdout, (r.returncode, r.stdout, r.stderr[-500:])
+
+
+def test_randomized_reclaims_against_the_oracle(oracle):
+    """Forty seeded random pools: sizes, odd tile sizes, layouts, occupancies, boundaries and
+    launch shapes drawn at random; plan, tables and every pool byte compared with the oracle."""
+    rs = np.random.default_rng(20251209)
+    for case in range(40):
+        nb = int(rs.integers(1, 3000))
+        b = int(rs.integers(0, nb + 1))
+        layers = int(rs.integers(1, 7))
+        tile = 16 * int(rs.integers(1, 600))
+        layer_major = bool(rs.integers(0, 2))
+        pad = 256 * int(rs.integers(0, 4)) if layer_major else 0
+        stride = -(-(nb * tile) // 256) * 256 + pad if layer_major else 0
+        live_bits = rs.random(nb) < rs.uniform(0.05, 0.6)
+        ids = np.flatnonzero(live_bits)
+        live = bitmap_from_ids(ids, nb)
+        p = oracle.plan(live, nb, b)
+        pool_bytes = layers * stride if layer_major else nb * layers * tile
+        pool0 = rs.integers(0, 256, pool_bytes, dtype=np.uint8)
+        rows = int(rs.integers(1, 20))
+        cols = int(rs.integers(1, 40))
+        tables = (rs.choice(np.concatenate([ids, [-1]]), size=(rows, cols)) if ids.size else
+                  np.full((rows, cols), -1)).astype(np.int32)
+        want_pool, want_tables = pool0.copy(), tables.copy()
+        if layer_major:
+            oracle.compact_layer_major(want_pool, tile, layers, stride, p)
+        else:
+            oracle.compact(want_pool, layers * tile, p)
+        bad = oracle.remap(want_tables, p)
+        tuning = dict(workgroups=int(rs.choice([0, 1, 3, 64, 256, 1000])), chunk_bytes=4096 * int(rs.integers(1, 40)),
+                      flags=(int(rs.choice([2, 4, 8, 16, 32])) << 4) | int(rs.integers(0, 8)))
+        _say(f"[random {case}] NB={nb} b={b} L={layers} tile={tile} layer_major={layer_major} stride={stride} "
+             f"status={p.status} n={p.n_moves} tuning={tuning}")
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, nb, layers, tile, stride)
+        dp = gh.DevicePlan(nb, b)
+        tables_dev = torch.from_numpy(tables).to(gh.dev())
+        live_dev = gh.to_dev(live)
+        wk.kv_plan_reclaim(live_dev, dp.plan)
+        wk.kv_compact_launch(pool, dp.plan, **tuning)
+        wk.kv_remap_tables(tables_dev, rows, cols, dp.plan)
+        torch.cuda.synchronize()
+        st = _compare_plan(dp, p)
+        assert st.n_bad_entries == bad and st.ticket == 0 and st.finished == 0
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), case
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), case

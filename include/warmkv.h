@@ -139,7 +139,11 @@ typedef struct kv_compact_tuning {
   uint32_t chunk_bytes;    /* bytes per work ticket; multiple of 4096 (default 65536)    */
   uint32_t flags;          /* bit 0: plain (cached) instead of non-temporal accesses;
                               bit 1: draw the next ticket during the copy, not after it;
-                              bit 2: layer-major pools: move by move instead of slab by slab;
+                              bit 2: layer-major pools: move by move instead of slab by slab
+                                     (tiles above half a ticket only);
+                              bit 3: one ticket per tile or block even when it is half a ticket
+                                     or less (default: such small units are packed, several
+                                     consecutive moves to a ticket of at most 64 KiB);
                               bits 4-9: 128-bit loads in flight per lane: 2, 4, 8, 16 (default)
                                         or 32                                              */
   uint32_t reserved;

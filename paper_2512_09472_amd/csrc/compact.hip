@@ -197,6 +197,95 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
   }
 }
 
+// Small segments (half a ticket or less: tiles of a layer-major pool with few
+// heads, blocks of a one-layer pool).  One ticket per segment would be drawn
+// faster than one counter address can hand them out (16 KiB units ran at 40 %
+// of the 64 KiB rate, 4 KiB units at 10 %), so a ticket here covers `pack`
+// consecutive moves of one segment: up to 64 KiB again, the same burst per
+// lane, and consecutive moves have ascending sources and destinations, so the
+// window still advances in order.  Lane i resolves move i of the ticket into
+// LDS; every lane then finds the move of each of its vectors by a multiply-high
+// with a host-made reciprocal.
+constexpr uint32_t kMaxPack = 256;   // moves per ticket: one lane resolves one move
+constexpr uint32_t kPackRows = 16;   // 128-bit accesses per lane per ticket (64 KiB per workgroup)
+constexpr uint64_t kSkip = ~0ull;    // LDS marker of a move that failed the src >= boundary > dst check
+
+struct PackArgs {
+  uint8_t* base;
+  uint64_t block_stride;
+  uint64_t seg_stride;
+  const int32_t* src;
+  const int32_t* dst;
+  kv_plan_state* state;
+  uint32_t num_blocks;
+  uint32_t boundary;
+  uint32_t segs;       // segments per move (layers of a layer-major pool, else 1)
+  uint32_t seg_vecs;   // 128-bit vectors per segment
+  uint32_t recip;      // ceil(2^32 / seg_vecs); v / seg_vecs == mulhi(v, recip) for v < 2^16 (unused if seg_vecs == 1)
+  uint32_t pack;       // moves per ticket, 2..kMaxPack, pack * seg_vecs <= kPackRows * kCopyThreads
+};
+
+template <bool NT>
+__global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a) {
+  const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
+  const uint32_t groups = (n_moves + a.pack - 1u) / a.pack;  // tickets per segment
+  const uint32_t n_units = groups * a.segs;                  // host checked: fits 31 bits
+  const uint32_t tid = threadIdx.x;
+  __shared__ uint32_t s_ticket;
+  __shared__ uint64_t s_src[kMaxPack], s_dst[kMaxPack];
+  for (;;) {
+    if (tid == 0) s_ticket = atomicAdd(&a.state->ticket, 1u);
+    __syncthreads();
+    const uint32_t ticket = uniform32(s_ticket);
+    if (ticket >= n_units) break;
+    // All tickets of segment (layer) 0, then of segment 1, ...
+    const uint32_t g = ticket / groups;
+    const uint32_t k0 = (ticket - g * groups) * a.pack;
+    const uint32_t cnt = n_moves - k0 < a.pack ? n_moves - k0 : a.pack;
+    if (tid < cnt) {
+      const uint32_t s = (uint32_t)a.src[k0 + tid], d = (uint32_t)a.dst[k0 + tid];
+      const bool ok = s >= a.boundary && s < a.num_blocks && d < a.boundary;  // always true for a planner-made plan
+      if (!ok) atomicExch(&a.state->status, KV_E_BADPLAN);
+      const uint64_t seg_off = (uint64_t)g * a.seg_stride;
+      s_src[tid] = ok ? (uint64_t)s * a.block_stride + seg_off : kSkip;
+      s_dst[tid] = (uint64_t)d * a.block_stride + seg_off;
+    }
+    __syncthreads();
+    const uint32_t n_vecs = cnt * a.seg_vecs;
+    u32x4 v[kPackRows];
+    uint64_t to[kPackRows];
+#pragma unroll
+    for (uint32_t j = 0; j < kPackRows; ++j) {
+      const uint32_t idx = tid + j * kCopyThreads;
+      to[j] = kSkip;
+      if (idx < n_vecs) {
+        const uint32_t m = a.seg_vecs == 1u ? idx : __umulhi(idx, a.recip);
+        const uint64_t within = (uint64_t)(idx - m * a.seg_vecs) * kVecBytes;
+        const uint64_t from = s_src[m];
+        if (from != kSkip) {
+          v[j] = load16<NT>((const u32x4*)(a.base + from + within));
+          to[j] = s_dst[m] + within;
+        }
+      }
+    }
+    // Read burst, then write burst, as in copy_rows.
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (uint32_t j = 0; j < kPackRows; ++j)
+      if (to[j] != kSkip) store16<NT>((u32x4*)(a.base + to[j]), v[j]);
+    __syncthreads();  // s_src / s_dst / s_ticket are rewritten by the next round
+  }
+  if (tid == 0) {  // sign out; the last workgroup re-arms the counters (see compact_ticket_kernel)
+    const uint32_t out = atomicAdd(&a.state->finished, 1u);
+    if (out == gridDim.x - 1u) {
+      atomicExch(&a.state->ticket, 0u);
+      atomicExch(&a.state->finished, 0u);
+    }
+  }
+}
+
 template <int UNROLL>
 int launch(const CopyArgs& a, uint32_t workgroups, bool nt, bool prefetch, hipStream_t s) {
   const dim3 grid(workgroups), block(kCopyThreads);
@@ -272,6 +361,29 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
   const bool nt = (flags & 1u) == 0;
   const bool prefetch = (flags & 2u) != 0;
   hipStream_t s = (hipStream_t)stream;
+
+  // Segments of half a ticket or less: several moves per ticket.
+  const uint32_t ticket_bytes = chunk < kPackRows * kRowBytes ? chunk : kPackRows * kRowBytes;
+  if ((flags & 8u) == 0 && a.seg_bytes * 2u <= ticket_bytes) {
+    PackArgs p;
+    p.base = a.base;
+    p.block_stride = a.block_stride;
+    p.seg_stride = a.seg_stride;
+    p.src = a.src;
+    p.dst = a.dst;
+    p.state = a.state;
+    p.num_blocks = a.num_blocks;
+    p.boundary = a.boundary;
+    p.segs = (uint32_t)segs;
+    p.seg_vecs = (uint32_t)(a.seg_bytes / kVecBytes);
+    p.recip = p.seg_vecs > 1u ? (uint32_t)(0xFFFFFFFFull / p.seg_vecs) + 1u : 0u;
+    const uint32_t fit = ticket_bytes / (uint32_t)a.seg_bytes;
+    p.pack = fit < kMaxPack ? fit : kMaxPack;
+    const dim3 grid(workgroups), block(kCopyThreads);
+    if (nt) hipLaunchKernelGGL((compact_packed_kernel<true>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((compact_packed_kernel<false>), grid, block, 0, s, p);
+    return launch_rc();
+  }
   switch (unroll) {
     case 2: return launch<2>(a, workgroups, nt, prefetch, s);
     case 4: return launch<4>(a, workgroups, nt, prefetch, s);

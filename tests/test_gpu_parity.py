@@ -46,6 +46,10 @@ SCALED = {
     "cfg4_odd_boundary": CONFIGS[3].scaled(num_blocks=1536, num_layers=4, num_seqs=128),
     "cfg5_frag": CONFIGS[4].scaled(num_blocks=4096, num_layers=2, num_seqs=1024),
     "cfg5_tiny_tile": CONFIGS[4].scaled(num_blocks=2048, num_layers=1, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512),
+    # blocks of half a ticket or less: several moves share one ticket of the block copy
+    "one_layer_16k_blocks": CONFIGS[1].scaled(num_blocks=3000, num_layers=1, kv_heads=2, num_seqs=60),
+    "one_layer_7680_blocks": CONFIGS[1].scaled(num_blocks=2500, num_layers=1, kv_heads=3, head_dim=40, num_seqs=50),
+    "two_layer_288_blocks": CONFIGS[4].scaled(num_blocks=5000, num_layers=2, block_size=1, kv_heads=1, head_dim=72, len_hi=16, num_seqs=900),
     # more than 65 536 blocks: the planner's several-workgroup shape plus its join kernel feed the copy
     "many_small_blocks": CONFIGS[4].scaled(num_blocks=150_000, num_layers=2, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=6000),
 }
@@ -56,7 +60,9 @@ TUNINGS = [None,                                                        # defaul
            dict(workgroups=7, chunk_bytes=8192, flags=2 << 4),
            dict(workgroups=3000, chunk_bytes=32768, flags=4 << 4),      # more workgroups than fit at once
            dict(workgroups=5000, chunk_bytes=32768, flags=(4 << 4) | 2),   # next ticket drawn during the copy
-           dict(workgroups=256, chunk_bytes=1 << 20, flags=(32 << 4) | 2)]
+           dict(workgroups=256, chunk_bytes=1 << 20, flags=(32 << 4) | 2),
+           dict(flags=8),                                               # small blocks: one ticket each, not packed
+           dict(workgroups=40, chunk_bytes=16384, flags=1)]             # small blocks packed into 16 KiB tickets
 
 
 @pytest.mark.parametrize("name", list(SCALED))
@@ -396,6 +402,9 @@ LAYER_MAJOR = {
     "lm_padded_slabs": (CONFIGS[3].scaled(num_blocks=1536, num_layers=4, num_seqs=128), 4096),
     "lm_ragged_tile": (CONFIGS[1].scaled(num_blocks=900, num_layers=5, kv_heads=3, head_dim=40, num_seqs=40), 256),
     "lm_tiny_tile": (CONFIGS[4].scaled(num_blocks=2048, num_layers=6, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512), 0),
+    # tiles of half a ticket or less: several moves of one slab share a ticket
+    "lm_16k_tile": (CONFIGS[1].scaled(num_blocks=1100, num_layers=3, kv_heads=2, num_seqs=50), 0),
+    "lm_7680_tile": (CONFIGS[1].scaled(num_blocks=1300, num_layers=4, kv_heads=3, head_dim=40, num_seqs=50), 512),
 }
 
 
@@ -434,7 +443,8 @@ def test_layer_major_reclaim_matches_oracle(oracle, name):
                                      [(h.numpy(), o) for h, o in zip(hosts, offs)]) == 0
     for tuning in (None, dict(chunk_bytes=4096, flags=2 << 4), dict(workgroups=3000, chunk_bytes=16384, flags=4 << 4),
                    dict(workgroups=512, chunk_bytes=32768, flags=(2 << 4) | 2), dict(flags=4),
-                   dict(workgroups=100, chunk_bytes=8192, flags=(2 << 4) | 2 | 4)):
+                   dict(workgroups=100, chunk_bytes=8192, flags=(2 << 4) | 2 | 4), dict(flags=8), dict(flags=8 | 4),
+                   dict(workgroups=33, chunk_bytes=32768)):
         _say(f"[layer-major] {name} tile={cfg.tile_bytes} L={cfg.num_layers} NB={cfg.num_blocks} pad={pad} tuning={tuning}")
         pool_dev = torch.from_numpy(pool0).to(gh.dev())
         pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, stride)

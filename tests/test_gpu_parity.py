@@ -231,9 +231,10 @@ def test_remap_table_shapes(oracle):
     assert dp.state().n_bad_entries == 0
 
 
-def test_hand_built_bad_plan_is_refused_per_move():
+@pytest.mark.parametrize("kv_heads", [8, 1])   # 64 KiB blocks: one ticket each; 8 KiB blocks: both moves in one ticket
+def test_hand_built_bad_plan_is_refused_per_move(kv_heads):
     """A move that breaks src >= boundary > dst is skipped and flagged; valid moves still run."""
-    cfg = CONFIGS[0].scaled(num_blocks=64, boundary=32)
+    cfg = CONFIGS[0].scaled(num_blocks=64, boundary=32, kv_heads=kv_heads)
     pool0 = gh.host_pool(cfg, gh.content_table(cfg))
     pool_dev = torch.from_numpy(pool0).to(gh.dev())
     dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)

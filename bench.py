@@ -59,6 +59,9 @@ def parse_args():
                          "(hipMemcpy DtoD through torch) as a reference point")
     ap.add_argument("--layout", choices=("block", "layer"), default="block",
                     help="pool layout: block-major (default) or layer-major (one slab per layer)")
+    ap.add_argument("--kv-heads", type=int, default=0,
+                    help="override the config's KV heads per block (a tensor-parallel share has fewer: smaller "
+                         "tiles, same block count); 0 = as the config says")
     ap.add_argument("--vmm-compare", type=int, default=0, metavar="BLOCKS",
                     help="also time the no-move variant (HIP virtual-memory remapping of unused blocks' pages) on a "
                          "pool of this many blocks of the config's shape; 20480 = the full 8B-shaped pool, which "
@@ -138,6 +141,8 @@ def main():
     wk.binding.load()
     dev = torch.device("cuda:0")
     cfg = CONFIGS[args.config]
+    if args.kv_heads:
+        cfg = cfg.scaled(kv_heads=args.kv_heads)
     w = make_workload(cfg)
     bb = cfg.block_bytes
 
@@ -205,6 +210,11 @@ def main():
     assert st.status == wk.KV_OK and st.n_moves == n_moves and st.n_bad_entries == 0
 
     reclaimed_bytes = (cfg.num_blocks - cfg.boundary) * bb
+    # which block-copy kernel the library picked: units of half a ticket or less share tickets
+    unit_bytes = cfg.tile_bytes if args.layout == "layer" else bb
+    ticket_bytes = min(args.chunk_bytes or 65536, 65536)
+    copy_kernel = ("compact_packed_kernel" if 2 * unit_bytes <= ticket_bytes and not args.flags & 8
+                   else "compact_ticket_kernel")
     out = {
         "metric": "KV compaction GB/s (read+write)",
         "value": round(rw_bytes / (ms_per_step * 1e-3) / 1e9, 2),
@@ -223,11 +233,12 @@ def main():
                    "pct_of_hbm_peak_whole_step": round(100 * rw_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBPS, 2),
                    "layout": args.layout + "-major", "tuning": tuning,
                    "inputs_sha256": hashlib.sha256(w.live.tobytes() + w.tables.tobytes()).hexdigest()[:16]},
-        "roofline": {"bound": "hbm", "kernel": "compact_ticket_kernel",
+        "roofline": {"bound": "hbm", "kernel": copy_kernel,
                      "achieved": round(rw_bytes / (compact_avg * 1e-3) / 1e9, 2), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(rw_bytes / (compact_avg * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                      "traffic": (MEASURED_TRAFFIC_BYTES.get((cfg.index, n_moves))
-                                 if not any(tuning.values()) and args.layout == "block" else None),
+                                 if not any(tuning.values()) and args.layout == "block" and not args.kv_heads
+                                 else None),
                      "kernel_ms_avg": round(compact_avg, 4), "kernel_ms_min": round(min(compact_ms), 4),
                      "kernel_ms_median": round(statistics.median(compact_ms), 4),
                      "algorithmic_bytes_per_launch": rw_bytes},
@@ -251,7 +262,7 @@ def main():
         torch.cuda.synchronize()
 
     # ---- weight materialisation leg (third configuration: same pool plus weights)
-    if not args.no_materialize and cfg.index in (1, 2) and args.layout == "block":
+    if not args.no_materialize and cfg.index in (1, 2) and args.layout == "block" and not args.kv_heads:
         shapes = weight_shapes_8b()
         sizes = [2 * a * b for _, (a, b) in shapes]
         offs = dense_offsets(sizes)

@@ -203,11 +203,19 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
 // of the 64 KiB rate, 4 KiB units at 10 %), so a ticket here covers `pack`
 // consecutive moves of one segment: up to 64 KiB again, the same burst per
 // lane, and consecutive moves have ascending sources and destinations, so the
-// window still advances in order.  Lane i resolves move i of the ticket into
-// LDS; every lane then finds the move of each of its vectors by a multiply-high
-// with a host-made reciprocal.
-constexpr uint32_t kMaxPack = 256;   // moves per ticket: one lane resolves one move
-constexpr uint32_t kPackRows = 16;   // 128-bit accesses per lane per ticket (64 KiB per workgroup)
+// window still advances in order.  The first wavefront draws the ticket and
+// resolves its moves into LDS (lane i: move i); every lane knows from the start
+// which move of a ticket each of its vectors belongs to (tickets begin at a move
+// boundary), found once by a multiply-high with a host-made reciprocal.
+//
+// The copy of a whole ticket is straight-line code with no predicate: a
+// conditional load or store costs a branch, and the wait the compiler puts at
+// each join serialises the burst (measured 10 % slower).  ROWS is the number of
+// 4 KiB rows a whole ticket takes; where the last row is only part filled, its
+// idle lanes repeat a vector of the same ticket (same bytes to the same place,
+// harmless) instead of being masked off.
+constexpr uint32_t kMaxPack = 256;   // moves per ticket: what one LDS table holds
+constexpr uint32_t kPackRows = 16;   // 128-bit accesses per lane per ticket at most (64 KiB per workgroup)
 constexpr uint64_t kSkip = ~0ull;    // LDS marker of a move that failed the src >= boundary > dst check
 
 struct PackArgs {
@@ -219,63 +227,103 @@ struct PackArgs {
   kv_plan_state* state;
   uint32_t num_blocks;
   uint32_t boundary;
-  uint32_t segs;       // segments per move (layers of a layer-major pool, else 1)
-  uint32_t seg_vecs;   // 128-bit vectors per segment
-  uint32_t recip;      // ceil(2^32 / seg_vecs); v / seg_vecs == mulhi(v, recip) for v < 2^16 (unused if seg_vecs == 1)
-  uint32_t pack;       // moves per ticket, 2..kMaxPack, pack * seg_vecs <= kPackRows * kCopyThreads
+  uint32_t segs;         // segments per move (layers of a layer-major pool, else 1)
+  uint32_t seg_vecs;     // 128-bit vectors per segment
+  uint32_t recip;        // ceil(2^32 / seg_vecs); v / seg_vecs == mulhi(v, recip) for v < 2^16 (unused if seg_vecs == 1)
+  uint32_t pack;         // moves per ticket, 2..kMaxPack
+  uint32_t ticket_vecs;  // pack * seg_vecs, in (ROWS-1)*256 .. ROWS*256
 };
 
-template <bool NT>
+template <bool NT, int ROWS>
 __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a) {
   const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
   const uint32_t groups = (n_moves + a.pack - 1u) / a.pack;  // tickets per segment
   const uint32_t n_units = groups * a.segs;                  // host checked: fits 31 bits
   const uint32_t tid = threadIdx.x;
-  __shared__ uint32_t s_ticket;
+  constexpr uint32_t kWholeTicket = ~0u;  // a.pack moves, none refused
+  __shared__ uint32_t s_ticket, s_count;  // s_count: moves of the ticket, or kWholeTicket
   __shared__ uint64_t s_src[kMaxPack], s_dst[kMaxPack];
-  for (;;) {
-    if (tid == 0) s_ticket = atomicAdd(&a.state->ticket, 1u);
-    __syncthreads();
-    const uint32_t ticket = uniform32(s_ticket);
-    if (ticket >= n_units) break;
-    // All tickets of segment (layer) 0, then of segment 1, ...
-    const uint32_t g = ticket / groups;
-    const uint32_t k0 = (ticket - g * groups) * a.pack;
-    const uint32_t cnt = n_moves - k0 < a.pack ? n_moves - k0 : a.pack;
-    if (tid < cnt) {
-      const uint32_t s = (uint32_t)a.src[k0 + tid], d = (uint32_t)a.dst[k0 + tid];
-      const bool ok = s >= a.boundary && s < a.num_blocks && d < a.boundary;  // always true for a planner-made plan
-      if (!ok) atomicExch(&a.state->status, KV_E_BADPLAN);
-      const uint64_t seg_off = (uint64_t)g * a.seg_stride;
-      s_src[tid] = ok ? (uint64_t)s * a.block_stride + seg_off : kSkip;
-      s_dst[tid] = (uint64_t)d * a.block_stride + seg_off;
-    }
-    __syncthreads();
-    const uint32_t n_vecs = cnt * a.seg_vecs;
-    u32x4 v[kPackRows];
-    uint64_t to[kPackRows];
+
+  uint32_t move_of[ROWS], within[ROWS];  // per vector of this lane: move of the ticket, byte offset in the segment
 #pragma unroll
-    for (uint32_t j = 0; j < kPackRows; ++j) {
-      const uint32_t idx = tid + j * kCopyThreads;
-      to[j] = kSkip;
-      if (idx < n_vecs) {
-        const uint32_t m = a.seg_vecs == 1u ? idx : __umulhi(idx, a.recip);
-        const uint64_t within = (uint64_t)(idx - m * a.seg_vecs) * kVecBytes;
-        const uint64_t from = s_src[m];
-        if (from != kSkip) {
-          v[j] = load16<NT>((const u32x4*)(a.base + from + within));
-          to[j] = s_dst[m] + within;
+  for (int j = 0; j < ROWS; ++j) {
+    uint32_t idx = tid + (uint32_t)j * kCopyThreads;
+    if (idx >= a.ticket_vecs) idx %= a.ticket_vecs;  // idle lane of the last row: repeat another vector
+    const uint32_t m = a.seg_vecs == 1u ? idx : __umulhi(idx, a.recip);
+    move_of[j] = m;
+    within[j] = (idx - m * a.seg_vecs) * kVecBytes;
+  }
+
+  for (;;) {
+    if (tid < (uint32_t)kWave) {
+      uint32_t ticket = 0;
+      if (tid == 0) ticket = atomicAdd(&a.state->ticket, 1u);
+      ticket = uniform32(ticket);
+      uint32_t cnt = 0;
+      bool refused = false;
+      if (ticket < n_units) {
+        // All tickets of segment (layer) 0, then of segment 1, ...
+        const uint32_t g = ticket / groups;
+        const uint32_t k0 = (ticket - g * groups) * a.pack;
+        cnt = n_moves - k0 < a.pack ? n_moves - k0 : a.pack;
+        const uint64_t seg_off = (uint64_t)g * a.seg_stride;
+        for (uint32_t i = tid; i < cnt; i += kWave) {
+          const uint32_t s = (uint32_t)a.src[k0 + i], d = (uint32_t)a.dst[k0 + i];
+          const bool ok = s >= a.boundary && s < a.num_blocks && d < a.boundary;  // always true for a planner-made plan
+          if (!ok) {
+            atomicExch(&a.state->status, KV_E_BADPLAN);
+            refused = true;
+          }
+          s_src[i] = ok ? (uint64_t)s * a.block_stride + seg_off : kSkip;
+          s_dst[i] = (uint64_t)d * a.block_stride + seg_off;
         }
       }
+      const bool whole = cnt == a.pack && __ballot(refused) == 0ull;
+      if (tid == 0) {
+        s_ticket = ticket;
+        s_count = whole ? kWholeTicket : cnt;
+      }
     }
-    // Read burst, then write burst, as in copy_rows.
-    __builtin_amdgcn_sched_barrier(0);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
+    __syncthreads();
+    if (uniform32(s_ticket) >= n_units) break;
+    const uint32_t cnt = uniform32(s_count);
+    u32x4 v[ROWS];
+    uint64_t to[ROWS];
+    if (cnt == kWholeTicket) {
+      uint64_t from[ROWS];
 #pragma unroll
-    for (uint32_t j = 0; j < kPackRows; ++j)
-      if (to[j] != kSkip) store16<NT>((u32x4*)(a.base + to[j]), v[j]);
-    __syncthreads();  // s_src / s_dst / s_ticket are rewritten by the next round
+      for (int j = 0; j < ROWS; ++j) {
+        from[j] = s_src[move_of[j]] + within[j];
+        to[j] = s_dst[move_of[j]] + within[j];
+      }
+#pragma unroll
+      for (int j = 0; j < ROWS; ++j) v[j] = load16<NT>((const u32x4*)(a.base + from[j]));
+      // Read burst, then write burst, as in copy_rows.
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < ROWS; ++j) store16<NT>((u32x4*)(a.base + to[j]), v[j]);
+    } else {  // the short last ticket of a segment, or a ticket with a refused move
+#pragma unroll
+      for (int j = 0; j < ROWS; ++j) {
+        to[j] = kSkip;
+        if (move_of[j] < cnt) {
+          const uint64_t from = s_src[move_of[j]];
+          if (from != kSkip) {
+            v[j] = load16<NT>((const u32x4*)(a.base + from + within[j]));
+            to[j] = s_dst[move_of[j]] + within[j];
+          }
+        }
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int j = 0; j < ROWS; ++j)
+        if (to[j] != kSkip) store16<NT>((u32x4*)(a.base + to[j]), v[j]);
+    }
+    __syncthreads();  // the LDS words are rewritten by the next round
   }
   if (tid == 0) {  // sign out; the last workgroup re-arms the counters (see compact_ticket_kernel)
     const uint32_t out = atomicAdd(&a.state->finished, 1u);
@@ -284,6 +332,14 @@ __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a
       atomicExch(&a.state->finished, 0u);
     }
   }
+}
+
+template <int ROWS>
+int launch_packed(const PackArgs& p, uint32_t workgroups, bool nt, hipStream_t s) {
+  const dim3 grid(workgroups), block(kCopyThreads);
+  if (nt) hipLaunchKernelGGL((compact_packed_kernel<true, ROWS>), grid, block, 0, s, p);
+  else hipLaunchKernelGGL((compact_packed_kernel<false, ROWS>), grid, block, 0, s, p);
+  return launch_rc();
 }
 
 template <int UNROLL>
@@ -379,11 +435,27 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
     p.recip = p.seg_vecs > 1u ? (uint32_t)(0xFFFFFFFFull / p.seg_vecs) + 1u : 0u;
     const uint32_t fit = ticket_bytes / (uint32_t)a.seg_bytes;
     p.pack = fit < kMaxPack ? fit : kMaxPack;
-    const dim3 grid(workgroups), block(kCopyThreads);
-    if (nt) hipLaunchKernelGGL((compact_packed_kernel<true>), grid, block, 0, s, p);
-    else hipLaunchKernelGGL((compact_packed_kernel<false>), grid, block, 0, s, p);
-    return launch_rc();
+    p.ticket_vecs = p.pack * p.seg_vecs;
+    switch ((p.ticket_vecs + kCopyThreads - 1u) / kCopyThreads) {  // rows of a whole ticket
+      case 1: return launch_packed<1>(p, workgroups, nt, s);
+      case 2: return launch_packed<2>(p, workgroups, nt, s);
+      case 3: return launch_packed<3>(p, workgroups, nt, s);
+      case 4: return launch_packed<4>(p, workgroups, nt, s);
+      case 5: return launch_packed<5>(p, workgroups, nt, s);
+      case 6: return launch_packed<6>(p, workgroups, nt, s);
+      case 7: return launch_packed<7>(p, workgroups, nt, s);
+      case 8: return launch_packed<8>(p, workgroups, nt, s);
+      case 9: return launch_packed<9>(p, workgroups, nt, s);
+      case 10: return launch_packed<10>(p, workgroups, nt, s);
+      case 11: return launch_packed<11>(p, workgroups, nt, s);
+      case 12: return launch_packed<12>(p, workgroups, nt, s);
+      case 13: return launch_packed<13>(p, workgroups, nt, s);
+      case 14: return launch_packed<14>(p, workgroups, nt, s);
+      case 15: return launch_packed<15>(p, workgroups, nt, s);
+      default: return launch_packed<16>(p, workgroups, nt, s);
+    }
   }
+
   switch (unroll) {
     case 2: return launch<2>(a, workgroups, nt, prefetch, s);
     case 4: return launch<4>(a, workgroups, nt, prefetch, s);

@@ -322,6 +322,16 @@ def main():
             wk.weights_materialize_pipelined(pool, cfg.boundary, w.live, tensors, 0, cs, done.cuda_event)
             wk.kv_remap_tables(tables_d, w.tables.shape[0], w.tables.shape[1], plan, s)
 
+        # the link's measured ceiling: one plain pinned-to-device copy of 4 GiB into the same region
+        n_plain = min(4 << 30, total)
+        region0 = cfg.boundary * bb
+
+        def plain_copy():
+            with torch.cuda.stream(copy_stream):
+                pool_t[region0:region0 + n_plain].copy_(host[:n_plain], non_blocking=True)
+
+        plain_copy()
+        t_plain = timed(plain_copy)
         only_copy()
         t_copy = timed(only_copy)
         t_serial = timed(serial)
@@ -330,6 +340,7 @@ def main():
         out["materialize"] = {"workload": "configs[2]: 225 bf16 tensors, 15,009,316,864 B from pinned host memory",
                               "h2d_ms": round(t_copy, 2), "h2d_GBps": round(total / t_copy / 1e6, 2),
                               "link_peak_GBps": LINK_PEAK_GBPS,
+                              "link_measured_plain_copy_GBps": round(n_plain / t_plain / 1e6, 2),
                               "frac_of_link_peak": round(total / t_copy / 1e6 / LINK_PEAK_GBPS, 4),
                               "serial_reclaim_then_copy_ms": round(t_serial, 2),
                               "overlapped_ms": round(t_overlap, 2),

@@ -74,11 +74,32 @@ struct Unit {
   uint64_t dst_off;
 };
 
-// Lane 0 only: draw the next ticket from the device-wide counter and resolve
-// it to (move k, segment g, chunk c) and on to byte offsets.
-__device__ __forceinline__ Unit draw_unit(const CopyArgs& a, uint32_t n_moves, uint32_t n_units) {
+// Tickets.  Workgroup i starts with ticket i, which costs nothing; every later
+// ticket is gridDim.x plus a draw from the device-wide counter.  When all units
+// fit the first round (n_units <= gridDim.x: small pools) nobody draws, the
+// counters are never touched and no workgroup has to sign out: 256 workgroups
+// hitting one address take about 3 us per round, as much as the copy itself
+// on a pool of a few hundred blocks.
+__device__ __forceinline__ uint32_t next_ticket(kv_plan_state* state, uint32_t n_units) {
+  return n_units > gridDim.x ? gridDim.x + atomicAdd(&state->ticket, 1u) : n_units;
+}
+
+// Sign out after a failed draw; the last workgroup out puts both counters back
+// to zero for the next call on this plan.  Nothing to do if nobody drew.
+__device__ __forceinline__ void sign_out(kv_plan_state* state, uint32_t n_units) {
+  if (n_units <= gridDim.x) return;
+  const uint32_t out = atomicAdd(&state->finished, 1u);
+  if (out == gridDim.x - 1u) {
+    atomicExch(&state->ticket, 0u);
+    atomicExch(&state->finished, 0u);
+  }
+}
+
+// Lane 0 only: resolve a ticket to (move k, segment g, chunk c) and on to byte
+// offsets.
+__device__ __forceinline__ Unit resolve_unit(const CopyArgs& a, uint32_t ticket, uint32_t n_moves, uint32_t n_units) {
   Unit unit;
-  unit.ticket = atomicAdd(&a.state->ticket, 1u);
+  unit.ticket = ticket;
   unit.len = 0;
   unit.src_off = unit.dst_off = 0;
   if (unit.ticket >= n_units) return unit;
@@ -153,21 +174,21 @@ __device__ __forceinline__ void copy_bytes(const u32x4* __restrict__ sp, u32x4* 
   if (i < len / kVecBytes) store16<NT>(dp + i, load16<NT>(sp + i));  // partial last row
 }
 
-// Persistent workgroups; units are handed out in list order by one ticket
-// counter.  Lane 0 draws and resolves the next unit after the current one is
+// Persistent workgroups; units are handed out in list order, the first round by
+// workgroup index and the rest by one ticket counter.  Lane 0 draws and resolves the next unit after the current one is
 // copied (default) or while it is copied (PREFETCH); the others pick it up from
 // LDS.  Drawing ahead hides the atomic and the two id loads, yet measured 4 %
 // slower on every workload: the short pause between units keeps fewer bytes in
 // flight per compute unit, and the memory system is saturated either way.
 template <int UNROLL, bool NT, bool PREFETCH>
 __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a) {
-  // No early return: every workgroup must draw its one out-of-range ticket and
-  // sign out below, or the counters would not return to zero.
+  // No early return once tickets are drawn: every workgroup must draw its one
+  // out-of-range ticket and sign out below, or the counters would not return to zero.
   const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
   const uint32_t n_units = n_moves * a.units_per_move;  // host checked: fits 31 bits
   const uint32_t tid = threadIdx.x;
   __shared__ Unit s_unit[2];
-  if (tid == 0) s_unit[0] = draw_unit(a, n_moves, n_units);
+  if (tid == 0) s_unit[0] = resolve_unit(a, blockIdx.x, n_moves, n_units);
   __syncthreads();
   uint32_t slot = 0;
   for (;;) {
@@ -177,24 +198,17 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
     const uint64_t src_off = uniform64(s_unit[slot].src_off);
     const uint64_t dst_off = uniform64(s_unit[slot].dst_off);
     // The other slot was last read before the previous barrier: free to refill.
-    if (PREFETCH && tid == 0) s_unit[slot ^ 1u] = draw_unit(a, n_moves, n_units);
+    if (PREFETCH && tid == 0) s_unit[slot ^ 1u] = resolve_unit(a, next_ticket(a.state, n_units), n_moves, n_units);
     copy_bytes<UNROLL, NT>((const u32x4*)(a.base + src_off), (u32x4*)(a.base + dst_off), len, tid);
     if (!PREFETCH) {
       __syncthreads();
-      if (tid == 0) s_unit[slot ^ 1u] = draw_unit(a, n_moves, n_units);
+      if (tid == 0) s_unit[slot ^ 1u] = resolve_unit(a, next_ticket(a.state, n_units), n_moves, n_units);
     }
     __syncthreads();
     slot ^= 1u;
   }
-  // Every workgroup draws exactly one ticket >= n_units.  The last one out
-  // puts both counters back to zero for the next call on this plan.
-  if (tid == 0) {
-    const uint32_t out = atomicAdd(&a.state->finished, 1u);
-    if (out == gridDim.x - 1u) {
-      atomicExch(&a.state->ticket, 0u);
-      atomicExch(&a.state->finished, 0u);
-    }
-  }
+  // Every workgroup ends on exactly one ticket >= n_units.
+  if (tid == 0) sign_out(a.state, n_units);
 }
 
 // Small segments (half a ticket or less: tiles of a layer-major pool with few
@@ -254,10 +268,12 @@ __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a
     within[j] = (idx - m * a.seg_vecs) * kVecBytes;
   }
 
+  bool first = true;  // the first ticket is the workgroup's index, later ones are drawn
   for (;;) {
     if (tid < (uint32_t)kWave) {
-      uint32_t ticket = 0;
-      if (tid == 0) ticket = atomicAdd(&a.state->ticket, 1u);
+      uint32_t ticket = blockIdx.x;
+      if (!first && tid == 0) ticket = next_ticket(a.state, n_units);
+      first = false;
       ticket = uniform32(ticket);
       uint32_t cnt = 0;
       bool refused = false;
@@ -325,13 +341,7 @@ __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a
     }
     __syncthreads();  // the LDS words are rewritten by the next round
   }
-  if (tid == 0) {  // sign out; the last workgroup re-arms the counters (see compact_ticket_kernel)
-    const uint32_t out = atomicAdd(&a.state->finished, 1u);
-    if (out == gridDim.x - 1u) {
-      atomicExch(&a.state->ticket, 0u);
-      atomicExch(&a.state->finished, 0u);
-    }
-  }
+  if (tid == 0) sign_out(a.state, n_units);
 }
 
 template <int ROWS>

@@ -294,6 +294,38 @@ def test_materialize_matches_oracle_and_overlaps_compaction(oracle):
     assert np.array_equal(pool_dev.cpu().numpy(), want)
 
 
+def test_materialize_from_one_pinned_buffer(oracle):
+    """Tensors cut from one pinned buffer: neighbours that continue each other in host memory
+    and in the pool may go out as one request; a gap on either side, or another order, may not
+    change a byte."""
+    cfg = CONFIGS[2].scaled(num_blocks=256, num_layers=2, num_seqs=32)
+    bb = cfg.block_bytes
+    region_bytes = (cfg.num_blocks - cfg.boundary) * bb
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    sizes = [4096, 48, 3 * bb + 16, 1 << 20, 256, 2 * bb]
+    buf = torch.empty(sum(sizes) + 64, dtype=torch.uint8, pin_memory=True)
+    buf.numpy()[:] = content.item_bytes_host(0xC0A1, 0, -(-buf.numel() // 8) * 8, None)[:buf.numel()]
+    cuts = np.concatenate([[0], np.cumsum(sizes)])
+    cuts[5:] += 64                                  # a gap in host memory before the last two
+    views = [buf[int(cuts[i]):int(cuts[i]) + sz] for i, sz in enumerate(sizes)]
+    # pool offsets: 0,1,2 back to back; 3 after a gap; 4 right behind 3 (but host memory has the gap); 5 at the end
+    offs = [0, 4096, 4096 + 48, 8 * bb, 8 * bb + (1 << 20), region_bytes - 2 * bb]
+    for order in ([0, 1, 2, 3, 4, 5], [2, 0, 1, 5, 4, 3]):
+        want = pool0.copy()
+        assert oracle.materialize(want, cfg.boundary * bb, [(views[i].numpy(), offs[i]) for i in order]) == 0
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+        wk.weights_materialize(pool, cfg.boundary, [(views[i], sizes[i], offs[i]) for i in order])
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want), order
+        live = np.zeros((cfg.num_blocks + 63) // 64, dtype=np.uint64)      # nothing live: every piece is early
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+        wk.weights_materialize_pipelined(pool, cfg.boundary, live, [(views[i], sizes[i], offs[i]) for i in order], 1 << 40)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want), ("pipelined", order)
+
+
 def test_pipelined_materialize_matches_oracle(oracle):
     """Block-granular pipelining: early pieces go out before the compaction event, the rest
     after it; the pool must hold exactly what the oracle's plain copy produces."""

@@ -136,10 +136,12 @@ def test_byte_offsets_beyond_2_and_4_gib(oracle):
     torch.cuda.empty_cache()
 
 
-def test_full_size_layer_major_reclaim(oracle):
+@pytest.mark.parametrize("kv_heads", [8, 2, 3])
+def test_full_size_layer_major_reclaim(oracle, kv_heads):
     """The 8B-shaped pool kept layer-major (32 slabs of 1.25 GiB): every slab is checked in full
-    against the oracle's plan, slab by slab, with the device generator."""
-    cfg = CONFIGS[1]
+    against the oracle's plan, slab by slab, with the device generator.  With 2 or 3 KV heads per
+    block (a tensor-parallel share) the tiles are 16 or 24 KiB and several moves share a ticket."""
+    cfg = CONFIGS[1].scaled(kv_heads=kv_heads)
     free_b, _ = torch.cuda.mem_get_info()
     if free_b < cfg.pool_bytes + (4 << 30):
         pytest.skip("not enough device memory")

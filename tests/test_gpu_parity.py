@@ -559,6 +559,106 @@ def test_plan_can_be_reused_after_the_pool_changes(oracle):
     assert p3.n_moves == 3
 
 
+def test_draining_instance_life_cycle(oracle):
+    """The whole scenario of Sec. 3.3 on one small pool, device state chained from step to step
+    with no host copy in between: Eq. 4 gives the boundary; reclaim; weights go in; requests
+    finish; Eq. 4 gives a lower boundary; reclaim again from the bitmap and tables the first
+    round left on the device; more weights; then the reserve proves too small and the boundary
+    rises again.  The oracle runs the same chain on the host."""
+    cfg = CONFIGS[1].scaled(num_blocks=1024, num_layers=2, num_seqs=64, boundary=1024, live_budget_override=400)
+    w = make_workload(cfg)
+    nb, bb = cfg.num_blocks, cfg.block_bytes
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    running = int((w.tables[:, 0] >= 0).sum())
+    b1 = wk.kv_reserve_blocks(nb, w.live_count, running, 2 * running)
+    assert b1 == oracle.reserve_blocks(nb, w.live_count, running, 2 * running) and w.live_count <= b1 < nb
+
+    def weights(seed, sizes):
+        out = []
+        for i, sz in enumerate(sizes):
+            h = torch.empty(sz, dtype=torch.uint8, pin_memory=True)
+            h.numpy()[:] = content.item_bytes_host(seed, i, -(-sz // 8) * 8, None)[:sz]
+            out.append(h)
+        return out
+
+    # ---- host chain (oracle)
+    want_pool, want_tables = pool0.copy(), w.tables.copy()
+    p1 = oracle.plan(w.live, nb, b1)
+    assert p1.status == 0 and p1.n_moves > 0
+    oracle.compact(want_pool, bb, p1)
+    assert oracle.remap(want_tables, p1) == 0
+    region1 = (nb - b1) * bb
+    sizes1 = [region1 // 3 // 16 * 16, 4096, region1 // 4 // 16 * 16]
+    offs1 = [0, sizes1[0], region1 - sizes1[2]]
+    hosts1 = weights(0xA1, sizes1)
+    assert oracle.materialize(want_pool, b1 * bb, [(h.numpy(), o) for h, o in zip(hosts1, offs1)]) == 0
+    # every second running sequence finishes: its blocks become free, its row empty
+    done_rows = [r for r in range(want_tables.shape[0]) if want_tables[r, 0] >= 0][::2]
+    live2 = p1.live_out.copy()
+    for r in done_rows:
+        for e in want_tables[r][want_tables[r] >= 0].tolist():
+            live2[e // 64] &= ~(np.uint64(1) << np.uint64(e % 64))
+        want_tables[r] = -1
+    used2 = int(sum(bin(int(x)).count("1") for x in live2))
+    b2 = oracle.reserve_blocks(b1, used2, running - len(done_rows), 2 * running)   # capacity is what the first round kept
+    assert used2 <= b2 < b1
+    p2 = oracle.plan(live2, nb, b2)
+    assert p2.status == 0
+    oracle.compact(want_pool, bb, p2)
+    assert oracle.remap(want_tables, p2) == 0
+    sizes2 = [((b1 - b2) * bb) // 2 // 16 * 16]
+    hosts2 = weights(0xA2, sizes2)
+    assert oracle.materialize(want_pool, b2 * bb, [(hosts2[0].numpy(), 16)]) == 0
+    # the reserve proves too small: the boundary rises by 3 blocks; which tensors of the second model survive?
+    lost, ev, new_off = oracle.grow(bb, nb, b2, b2 + 3, [(sizes2[0], 16)])
+
+    # ---- device chain
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool = wk.pool_desc(pool_dev, nb, cfg.num_layers, cfg.tile_bytes)
+    tables_dev = torch.from_numpy(w.tables).to(gh.dev())
+    live_dev = gh.to_dev(w.live)
+    s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+    done = torch.cuda.Event()
+    dp1 = gh.DevicePlan(nb, b1)
+    torch.cuda.synchronize()
+    wk.kv_plan_reclaim(live_dev, dp1.plan, s_compute.cuda_stream)
+    wk.kv_compact(pool, dp1.plan, s_compute.cuda_stream)
+    done.record(s_compute)
+    wk.kv_remap_tables(tables_dev, *w.tables.shape, dp1.plan, s_compute.cuda_stream)
+    wk.weights_materialize(pool, b1, [(h, h.numel(), o) for h, o in zip(hosts1, offs1)], s_copy.cuda_stream,
+                           done.cuda_event)
+    # requests finish: the engine clears their bits and rows on the device (test code, torch ops)
+    with torch.cuda.stream(s_compute):
+        live_words = gh.view_device(dp1.plan.live_out, 8 * ((nb + 63) // 64)).view(torch.int64)
+        ids = tables_dev[done_rows].flatten()
+        ids = ids[ids >= 0].to(torch.int64)
+        clear = torch.zeros(nb, dtype=torch.bool, device=gh.dev())
+        clear[ids] = True
+        weights_of_bits = (torch.ones(64, dtype=torch.int64, device=gh.dev()) << torch.arange(64, device=gh.dev()))
+        pad = torch.zeros(live_words.numel() * 64, dtype=torch.bool, device=gh.dev())
+        pad[:nb] = clear
+        mask = (pad.view(-1, 64).to(torch.int64) * weights_of_bits).sum(dim=1)
+        live2_dev = live_words & ~mask
+        tables_dev[done_rows] = -1
+    dp2 = gh.DevicePlan(nb, b2)
+    done2 = torch.cuda.Event()
+    s_compute.wait_stream(s_copy)          # the second round reads and writes bytes the first weight stream may still touch
+    wk.kv_plan_reclaim(live2_dev.data_ptr(), dp2.plan, s_compute.cuda_stream)
+    wk.kv_compact(pool, dp2.plan, s_compute.cuda_stream)
+    done2.record(s_compute)
+    wk.kv_remap_tables(tables_dev, *w.tables.shape, dp2.plan, s_compute.cuda_stream)
+    wk.weights_materialize(pool, b2, [(hosts2[0], sizes2[0], 16)], s_copy.cuda_stream, done2.cuda_event)
+    torch.cuda.synchronize()
+    _compare_plan(dp1, p1)
+    _compare_plan(dp2, p2)
+    assert np.array_equal(gh.from_dev(live2_dev, np.uint64), live2)
+    assert np.array_equal(tables_dev.cpu().numpy(), want_tables)
+    assert np.array_equal(pool_dev.cpu().numpy(), want_pool)
+    assert int(tables_dev.max()) < b2
+    got_lost, got_ev, got_off = wk.kv_grow(pool, b2, b2 + 3, [(hosts2[0], sizes2[0], 16)])
+    assert (got_lost, got_ev, got_off) == (lost, ev.tolist(), new_off.tolist()) and lost == 1
+
+
 def test_reclaim_step_replays_from_a_hip_graph(oracle):
     """plan -> compact -> remap needs no host synchronisation and no memset, so the three launches
     can be captured once and replayed; every replay must give the oracle's result, with eager work

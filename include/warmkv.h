@@ -229,6 +229,40 @@ int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
                                   uint64_t early_bytes,
                                   void* copy_stream, void* compaction_done);
 
+/* One request for the whole hand-over (App. C, Fig. 4b steps 1-3). */
+typedef struct kv_switch_request {
+  const kv_pool_desc* pool;
+  const kv_plan*      plan;          /* bound by kv_plan_bind; its boundary is the reclaim boundary   */
+  const uint64_t*     live_in;       /* [device] live bitmap, as for kv_plan_reclaim                  */
+  const uint64_t*     live_host;     /* [host] the same bitmap, or NULL: weights wait for the whole
+                                        block copy instead of being pipelined block by block         */
+  int32_t*            tables;        /* [device] as for kv_remap_tables                               */
+  uint32_t            num_seqs;
+  uint32_t            max_blocks_per_seq;
+  const wm_tensor*    tensors;       /* [host] as for weights_materialize                             */
+  uint32_t            n_tensors;
+  uint32_t            reserved;
+  uint64_t            early_bytes;   /* as for weights_materialize_pipelined (0 = default)            */
+  void*               compute_stream;
+  void*               copy_stream;
+  void*               compaction_done;  /* hipEvent_t created by the caller; recorded by this call    */
+} kv_switch_request;
+
+/* The hand-over as one call: plan, block copy and table rewrite on
+ * compute_stream, the weight stream on copy_stream behind compaction_done
+ * (pipelined block by block if live_host is given and the pool is
+ * block-major).  Existing requests take precedence over prewarmed weights
+ * (Sec. 3.3): after the planner has run, compute_stream is synchronised once
+ * and its verdict read; if the request is infeasible the call returns
+ * KV_E_NOSPACE and nothing else is enqueued - no pool byte, table entry or
+ * weight byte moves.  (With the separate calls the caller has to make that
+ * check before weights_materialize, which would otherwise overwrite the blocks
+ * that could not move.)  All arguments, weight extents included, are validated
+ * before the planner is launched.  *result [host, may be NULL] receives the
+ * plan's header.  On KV_OK everything is enqueued and the call returns without
+ * waiting for it. */
+int kv_switch(const kv_switch_request* request, kv_plan_state* result);
+
 /* Reserved KV space of a draining instance, Sec. 3.3 Eq. 4, in blocks:
  * R = max(C*Q/B, T + C/B), fractional blocks rounded up, capped at C.
  * C = capacity_blocks (<= 2^32 - 1), T = used_blocks, Q = running requests,

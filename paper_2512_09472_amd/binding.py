@@ -31,7 +31,7 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
-           "weights_materialize_pipelined", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
+           "weights_materialize_pipelined", "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
            "ws_place_replicas", "warmkv_version")
 
@@ -69,6 +69,14 @@ class wm_tensor(Structure):
 class wm_piece(Structure):
     _fields_ = [("tensor", c_uint32), ("early", c_uint32), ("src_offset", c_uint64), ("dst_offset", c_uint64),
                 ("bytes", c_uint64)]
+
+
+class kv_switch_request(Structure):
+    _fields_ = [("pool", POINTER(kv_pool_desc)), ("plan", POINTER(kv_plan)), ("live_in", c_void_p),
+                ("live_host", c_void_p), ("tables", c_void_p), ("num_seqs", c_uint32),
+                ("max_blocks_per_seq", c_uint32), ("tensors", POINTER(wm_tensor)), ("n_tensors", c_uint32),
+                ("reserved", c_uint32), ("early_bytes", c_uint64), ("compute_stream", c_void_p),
+                ("copy_stream", c_void_p), ("compaction_done", c_void_p)]
 
 
 class ws_model(Structure):
@@ -119,6 +127,8 @@ def load():
     L.weights_materialize_pipelined.restype = c_int
     L.weights_materialize_pipelined.argtypes = [POINTER(kv_pool_desc), c_uint32, c_void_p, POINTER(wm_tensor), c_uint32,
                                                 c_uint64, c_void_p, c_void_p]
+    L.kv_switch.restype = c_int
+    L.kv_switch.argtypes = [POINTER(kv_switch_request), POINTER(kv_plan_state)]
     L.kv_reserve_blocks.restype = c_int64
     L.kv_reserve_blocks.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
     L.kv_grow.restype = c_int64
@@ -242,6 +252,22 @@ def weights_materialize_pipelined(pool: kv_pool_desc, boundary: int, live_host, 
     _check("weights_materialize_pipelined",
            load().weights_materialize_pipelined(byref(pool), boundary, live_ptr, arr, n, early_bytes,
                                                 _ptr(copy_stream), _ptr(compaction_done)))
+
+
+def kv_switch(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int, max_blocks_per_seq: int, tensors,
+              compute_stream, copy_stream, compaction_done, live_host=None, early_bytes: int = 0) -> kv_plan_state:
+    """The whole hand-over in one call; returns the plan's header.  Raises WarmKVError (KV_E_NOSPACE) if the
+    request is infeasible, in which case nothing was moved or sent."""
+    arr, n = _tensor_array(tensors)
+    live_host_ptr = None
+    if live_host is not None:
+        live_host_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
+    rq = kv_switch_request(ctypes.pointer(pool), ctypes.pointer(plan), _ptr(live_in), live_host_ptr, _ptr(tables),
+                           num_seqs, max_blocks_per_seq, arr, n, 0, early_bytes, _ptr(compute_stream),
+                           _ptr(copy_stream), _ptr(compaction_done))
+    st = kv_plan_state()
+    _check("kv_switch", load().kv_switch(byref(rq), byref(st)))
+    return st
 
 
 def kv_reserve_blocks(capacity_blocks: int, used_blocks: int, running: int, max_batch: int) -> int:

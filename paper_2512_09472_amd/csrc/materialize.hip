@@ -236,3 +236,44 @@ extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t 
   }
   return requests.flush();
 }
+
+// The whole hand-over in one call.  The separate entry points leave one gap
+// to the caller: an infeasible plan turns kv_compact and kv_remap_tables into
+// no-ops, but a weight stream enqueued behind them would still overwrite the
+// live blocks that could not move.  Here the plan's verdict is fetched (one
+// host synchronisation, microseconds against a weight stream of hundreds of
+// milliseconds) before anything that writes the pool is enqueued.
+extern "C" int kv_switch(const kv_switch_request* rq, kv_plan_state* result) {
+  if (rq == nullptr || rq->pool == nullptr || rq->plan == nullptr || rq->compaction_done == nullptr) return KV_E_NULL;
+  const kv_pool_desc* pool = rq->pool;
+  const kv_plan* plan = rq->plan;
+  if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
+  if (pool->num_layers == 0 || pool->tile_bytes == 0) return KV_E_RANGE;
+  if ((pool->tile_bytes % 16u) != 0 || ((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
+  const uint64_t n_entries = (uint64_t)rq->num_seqs * rq->max_blocks_per_seq;
+  if (n_entries != 0 && rq->tables == nullptr) return KV_E_NULL;
+  if (((uintptr_t)rq->tables % 16u) != 0) return KV_E_ALIGN;
+  Region r;
+  int rc = validate(pool, plan->boundary, rq->tensors, rq->n_tensors, &r);
+  if (rc != KV_OK) return rc;
+
+  rc = kv_plan_reclaim(rq->live_in, plan, rq->compute_stream);
+  if (rc != KV_OK) return rc;
+  kv_plan_state st;
+  rc = kv_plan_fetch(plan, rq->compute_stream, &st);
+  if (rc != KV_OK) return rc;
+  if (result != nullptr) *result = st;
+  if (st.status != KV_OK) return st.status;  // running requests keep their blocks; no weight byte is sent
+
+  rc = kv_compact(pool, plan, rq->compute_stream);
+  if (rc != KV_OK) return rc;
+  rc = hip_rc(hipEventRecord((hipEvent_t)rq->compaction_done, (hipStream_t)rq->compute_stream));
+  if (rc != KV_OK) return rc;
+  rc = kv_remap_tables(rq->tables, rq->num_seqs, rq->max_blocks_per_seq, plan, rq->compute_stream);
+  if (rc != KV_OK) return rc;
+  if (rq->live_host != nullptr && !r.layer_major && r.block_bytes != 0)
+    return weights_materialize_pipelined(pool, plan->boundary, rq->live_host, rq->tensors, rq->n_tensors,
+                                         rq->early_bytes, rq->copy_stream, rq->compaction_done);
+  return weights_materialize(pool, plan->boundary, rq->tensors, rq->n_tensors, rq->copy_stream,
+                             rq->compaction_done);
+}

@@ -37,6 +37,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.kv_compact_tuning) == 16
     assert ctypes.sizeof(binding.wm_tensor) == 24
     assert ctypes.sizeof(binding.wm_piece) == 32
+    assert ctypes.sizeof(binding.kv_switch_request) == 96
 
 
 def test_workspace_and_bind():
@@ -238,3 +239,30 @@ def test_header_is_valid_c99_and_cxx():
     h = os.path.join(ROOT, "include", "warmkv.h")
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", h], check=True)
     subprocess.run(["g++", "-std=c++17", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c++", h], check=True)
+
+
+def test_switch_rejects_bad_requests_before_touching_the_device():
+    """Every argument error of the one-call hand-over is found on the host, before the planner
+    is launched (no GPU here: a launch would fail differently)."""
+    nb, b, tile = 64, 40, 4096
+    need = wk.kv_plan_workspace_bytes(nb, b)
+    plan = wk.kv_plan_bind(FAKE, need, nb, b)
+    pool = wk.pool_desc(FAKE + (1 << 20), nb, 2, tile)
+    region = (nb - b) * 2 * tile
+    ok = dict(pool=pool, plan=plan, live_in=FAKE + 512, tables=FAKE + 1024, num_seqs=4, max_blocks_per_seq=8,
+              tensors=[(FAKE, 4096, 0)], compute_stream=0, copy_stream=0, compaction_done=FAKE)
+    cases = [
+        (dict(compaction_done=None), wk.KV_E_NULL),
+        (dict(pool=wk.pool_desc(FAKE + (1 << 20), nb + 1, 2, tile)), wk.KV_E_RANGE),
+        (dict(pool=wk.pool_desc(FAKE + (1 << 20), nb, 2, tile + 8)), wk.KV_E_ALIGN),
+        (dict(pool=wk.pool_desc(FAKE + (1 << 20) + 16, nb, 2, tile)), wk.KV_E_ALIGN),
+        (dict(tables=None), wk.KV_E_NULL),
+        (dict(tables=FAKE + 1028), wk.KV_E_ALIGN),
+        (dict(tensors=[(FAKE, region + 16, 0)]), wk.KV_E_TOOBIG),
+        (dict(tensors=[(FAKE, 4096, 0), (FAKE, 4096, 4095)]), wk.KV_E_OVERLAP),
+        (dict(tensors=[(None, 4096, 0)]), wk.KV_E_NULL),
+    ]
+    for change, code in cases:
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.kv_switch(**{**ok, **change})
+        assert e.value.code == code, change

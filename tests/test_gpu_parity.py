@@ -559,6 +559,63 @@ def test_plan_can_be_reused_after_the_pool_changes(oracle):
     assert p3.n_moves == 3
 
 
+@pytest.mark.parametrize("pipelined", [False, True])
+def test_switch_in_one_call(oracle, pipelined):
+    """kv_switch = plan + block copy + table rewrite + weight stream; byte-identical to the
+    oracle's steps.  An infeasible request comes back as KV_E_NOSPACE with no pool byte, table
+    entry or weight byte moved - the weights must not land on the blocks that could not move."""
+    cfg = CONFIGS[2].scaled(num_blocks=640, num_layers=2, num_seqs=48)
+    w = make_workload(cfg)
+    bb = cfg.block_bytes
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    region = (cfg.num_blocks - cfg.boundary) * bb
+    sizes = [region // 2 // 16 * 16, 4096, region // 8 // 16 * 16]
+    offs = [0, sizes[0], region - sizes[2]]
+    hosts = []
+    for i, sz in enumerate(sizes):
+        h = torch.empty(sz, dtype=torch.uint8, pin_memory=True)
+        h.numpy()[:] = content.item_bytes_host(0x51, i, -(-sz // 8) * 8, None)[:sz]
+        hosts.append(h)
+    tensors = [(h, h.numel(), o) for h, o in zip(hosts, offs)]
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want_pool, want_tables = pool0.copy(), w.tables.copy()
+    oracle.compact(want_pool, bb, p)
+    assert oracle.remap(want_tables, p) == 0
+    assert oracle.materialize(want_pool, cfg.boundary * bb, [(h.numpy(), o) for h, o in zip(hosts, offs)]) == 0
+
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    tables_dev = torch.from_numpy(w.tables).to(gh.dev())
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    live_dev = gh.to_dev(w.live)
+    s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+    done = torch.cuda.Event()
+    done.record(s_compute)                 # torch creates the HIP event lazily, on its first record
+    torch.cuda.synchronize()
+    st = wk.kv_switch(pool, dp.plan, live_dev, tables_dev, *w.tables.shape, tensors, s_compute.cuda_stream,
+                      s_copy.cuda_stream, done.cuda_event, live_host=w.live if pipelined else None)
+    assert st.status == 0 and st.n_moves == p.n_moves
+    torch.cuda.synchronize()
+    _compare_plan(dp, p)
+    assert np.array_equal(tables_dev.cpu().numpy(), want_tables)
+    assert np.array_equal(pool_dev.cpu().numpy(), want_pool)
+
+    # infeasible: more live blocks than fit under the boundary
+    full = cfg.scaled(live_budget_override=cfg.boundary + 7)
+    wf = make_workload(full)
+    assert oracle.plan(wf.live, cfg.num_blocks, cfg.boundary).status == oracle.E_NOSPACE
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    tables_dev = torch.from_numpy(wf.tables).to(gh.dev())
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.kv_switch(pool, dp.plan, gh.to_dev(wf.live), tables_dev, *wf.tables.shape, tensors, s_compute.cuda_stream,
+                     s_copy.cuda_stream, done.cuda_event, live_host=wf.live if pipelined else None)
+    assert e.value.code == wk.KV_E_NOSPACE
+    torch.cuda.synchronize()
+    assert np.array_equal(pool_dev.cpu().numpy(), pool0), "an infeasible hand-over must not write the pool"
+    assert np.array_equal(tables_dev.cpu().numpy(), wf.tables)
+
+
 def test_draining_instance_life_cycle(oracle):
     """The whole scenario of Sec. 3.3 on one small pool, device state chained from step to step
     with no host copy in between: Eq. 4 gives the boundary; reclaim; weights go in; requests

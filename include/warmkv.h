@@ -66,7 +66,9 @@ extern "C" {
  *   l*layer_stride_bytes + i*tile_bytes; layer_stride_bytes >= NB*tile_bytes
  *   and a multiple of 256.  A block is then L separate tiles and the reclaimed
  *   space is L strips, one per slab: bytes [b*tile_bytes, NB*tile_bytes) of
- *   each. */
+ *   each.  An engine that keeps K and V of a layer in two slabs of their own
+ *   describes 2L slabs of half-tiles (num_layers = 2L, tile_bytes = one K or
+ *   V tile) if the 2L slabs are equally spaced, else one pool per slab set. */
 typedef struct kv_pool_desc {
   void*    base;                /* [device] 256-byte aligned                           */
   uint32_t num_blocks;          /* NB, at most 2^24                                    */

@@ -80,6 +80,7 @@ extern "C" int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint
   if (n_tensors != 0 && (tensors == nullptr || evicted == nullptr || new_offset == nullptr)) return KV_E_NULL;
   if (old_boundary > new_boundary || new_boundary > pool->num_blocks) return KV_E_RANGE;
   if (pool->layer_stride_bytes != 0) return KV_E_RANGE;  // block-major pools only
+  if ((pool->tile_bytes != 0 && pool->num_layers != 0) && !pool_extent_ok(*pool)) return KV_E_RANGE;
   const uint64_t block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
   const uint64_t old_region = (uint64_t)(pool->num_blocks - old_boundary) * block_bytes;
   const uint64_t returned = (uint64_t)(new_boundary - old_boundary) * block_bytes;

@@ -18,6 +18,18 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? KV_OK : KV_E_HIP; }
 
+// True if every byte offset inside the described pool can be formed without
+// overflow: the whole extent stays below 2^48 bytes.
+inline bool pool_extent_ok(const kv_pool_desc& p) {
+  constexpr uint64_t kMax = 1ull << 48;
+  if (p.tile_bytes == 0 || p.num_layers == 0) return false;
+  if (p.tile_bytes > kMax / p.num_layers) return false;
+  const uint64_t per_block = p.tile_bytes * p.num_layers;
+  if (p.num_blocks != 0 && per_block > kMax / p.num_blocks) return false;
+  if (p.layer_stride_bytes > kMax / p.num_layers) return false;
+  return true;
+}
+
 // Launch status without clearing an earlier sticky error of the caller's.
 inline int launch_rc() { return hip_rc(hipGetLastError()); }
 

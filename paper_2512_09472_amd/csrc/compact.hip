@@ -6,8 +6,9 @@
 //
 // Shape.  The work list is (move, chunk) units of 64 KiB in list order (in a
 // layer-major pool a move is one tile per layer slab: (move, layer, chunk)).  One
-// 256-lane workgroup per compute unit stays resident and draws units from a
-// single device-wide ticket counter, so at any moment the 256 workgroups stream
+// 256-lane workgroup per compute unit stays resident and takes units in list
+// order (its own index first, then draws from a single device-wide ticket
+// counter), so at any moment the 256 workgroups stream
 // one narrow, advancing window (about 16 MiB of sources and as much of
 // destinations).  Measured on MI355X this ordering is what matters: a static
 // grid-stride assignment lets workgroups drift apart, the window smears over
@@ -371,7 +372,7 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
                                  const kv_compact_tuning* tuning, void* stream) {
   if (pool == nullptr || plan == nullptr || plan->state == nullptr) return KV_E_NULL;
   if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
-  if (pool->num_layers == 0 || pool->tile_bytes == 0) return KV_E_RANGE;
+  if (!pool_extent_ok(*pool)) return KV_E_RANGE;  // zero or absurd sizes
   if ((pool->tile_bytes % kVecBytes) != 0) return KV_E_ALIGN;
 
   uint32_t workgroups = 0, chunk = kDefaultChunk, flags = 0u;

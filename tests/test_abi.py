@@ -266,3 +266,18 @@ def test_switch_rejects_bad_requests_before_touching_the_device():
         with pytest.raises(wk.WarmKVError) as e:
             wk.kv_switch(**{**ok, **change})
         assert e.value.code == code, change
+
+
+def test_absurd_pool_sizes_are_refused():
+    """Sizes whose byte offsets would overflow 64 bits (or leave the 48-bit address space) are
+    argument errors, found before any launch."""
+    nb, b = 64, 40
+    plan = wk.kv_plan_bind(FAKE, wk.kv_plan_workspace_bytes(nb, b), nb, b)
+    for pool in (wk.pool_desc(FAKE + (1 << 20), nb, 2, 1 << 60), wk.pool_desc(FAKE + (1 << 20), nb, 1 << 20, 1 << 30),
+                 wk.pool_desc(FAKE + (1 << 20), nb, 4, 4096, 1 << 47)):
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.kv_compact(pool, plan)
+        assert e.value.code == wk.KV_E_RANGE
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.weights_materialize(pool, b, [(FAKE, 16, 0)])
+        assert e.value.code == wk.KV_E_RANGE

@@ -326,7 +326,7 @@ def main():
             with torch.cuda.stream(stream):
                 tables_d.copy_(tables0_d, non_blocking=True)
             wk.kv_switch(pool, plan, live_d, tables_d, w.tables.shape[0], w.tables.shape[1], tensors, s, cs,
-                         done.cuda_event, live_host=w.live)
+                         done.cuda_event, live_host=w.live, front_done=front_done.cuda_event)
 
         # the link's measured ceiling: one plain pinned-to-device copy of 4 GiB into the same region
         n_plain = min(4 << 30, total)
@@ -343,7 +343,9 @@ def main():
         t_serial = timed(serial)
         t_overlap = timed(overlapped)
         t_pipe = timed(pipelined)
-        done.record(stream)                # torch creates the HIP event on its first record
+        front_done = torch.cuda.Event()
+        done.record(stream)                # torch creates a HIP event on its first record
+        front_done.record(stream)
         t_switch = timed(one_call)
         out["materialize"] = {"workload": "configs[2]: 225 bf16 tensors, 15,009,316,864 B from pinned host memory",
                               "h2d_ms": round(t_copy, 2), "h2d_GBps": round(total / t_copy / 1e6, 2),

@@ -231,6 +231,32 @@ int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
                                   uint64_t early_bytes,
                                   void* copy_stream, void* compaction_done);
 
+/* Block copy of a part of the plan: moves [first_move, first_move + max_moves)
+ * that exist (k < n_moves); otherwise as kv_compact.  Moves are listed in
+ * ascending source order, so "the first h moves" are the movers of the first
+ * blocks of the reclaimed region. */
+int kv_compact_moves(const kv_pool_desc* pool, const kv_plan* plan, uint32_t first_move,
+                     uint32_t max_moves, void* stream);
+
+/* Number of live blocks among the first front_blocks blocks at and above
+ * `boundary` in live_host [host bitmap, as given to kv_plan_reclaim]: how many
+ * moves of a feasible plan evacuate that front.  Host arithmetic only. */
+uint32_t kv_movers_in_front(const uint64_t* live_host, uint32_t num_blocks, uint32_t boundary,
+                            uint32_t front_blocks);
+
+/* Front-first weight stream (a copy starts once its destination is ready,
+ * App. C): the block copy frees the reclaimed region from its start, so the
+ * bytes of every tensor that lie below region offset front_bytes are enqueued
+ * behind front_done (hipEvent_t recorded after kv_compact_moves(0, h), h =
+ * kv_movers_in_front(.., ceil(front_bytes / block_bytes))) and the remaining
+ * bytes behind compaction_done (recorded after the rest of the block copy).
+ * Either event may be NULL (no wait).  Same validation, same bytes in the pool
+ * as weights_materialize; each tensor is cut at most once.  Block-major pools
+ * only (KV_E_RANGE otherwise). */
+int weights_materialize_front(const kv_pool_desc* pool, uint32_t boundary, uint64_t front_bytes,
+                              const wm_tensor* tensors, uint32_t n_tensors,
+                              void* copy_stream, void* front_done, void* compaction_done);
+
 /* One request for the whole hand-over (App. C, Fig. 4b steps 1-3). */
 typedef struct kv_switch_request {
   const kv_pool_desc* pool;
@@ -248,12 +274,18 @@ typedef struct kv_switch_request {
   void*               compute_stream;
   void*               copy_stream;
   void*               compaction_done;  /* hipEvent_t created by the caller; recorded by this call    */
+  void*               front_done;    /* second hipEvent_t of the caller's, or NULL; with live_host it
+                                        selects the front-first weight stream (see below)            */
 } kv_switch_request;
 
 /* The hand-over as one call: plan, block copy and table rewrite on
- * compute_stream, the weight stream on copy_stream behind compaction_done
- * (pipelined block by block if live_host is given and the pool is
- * block-major).  Existing requests take precedence over prewarmed weights
+ * compute_stream, the weight stream on copy_stream behind compaction_done.
+ * If live_host is given and the pool is block-major the weight stream is
+ * pipelined with the block copy: front first if front_done is given too (the
+ * block copy is launched in two parts, the movers under the first early_bytes
+ * of the region and the rest, with front_done recorded in between; early_bytes
+ * 0 = sized from the plan so that the link stays busy until the block copy has
+ * ended), else block by block as in weights_materialize_pipelined.  Existing requests take precedence over prewarmed weights
  * (Sec. 3.3): after the planner has run, compute_stream is synchronised once
  * and its verdict read; if the request is infeasible the call returns
  * KV_E_NOSPACE and nothing else is enqueued - no pool byte, table entry or

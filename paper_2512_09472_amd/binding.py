@@ -31,7 +31,8 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
-           "weights_materialize_pipelined", "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
+           "weights_materialize_pipelined", "kv_compact_moves", "kv_movers_in_front", "weights_materialize_front",
+           "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
            "ws_place_replicas", "warmkv_version")
 
@@ -76,7 +77,7 @@ class kv_switch_request(Structure):
                 ("live_host", c_void_p), ("tables", c_void_p), ("num_seqs", c_uint32),
                 ("max_blocks_per_seq", c_uint32), ("tensors", POINTER(wm_tensor)), ("n_tensors", c_uint32),
                 ("reserved", c_uint32), ("early_bytes", c_uint64), ("compute_stream", c_void_p),
-                ("copy_stream", c_void_p), ("compaction_done", c_void_p)]
+                ("copy_stream", c_void_p), ("compaction_done", c_void_p), ("front_done", c_void_p)]
 
 
 class ws_model(Structure):
@@ -127,6 +128,13 @@ def load():
     L.weights_materialize_pipelined.restype = c_int
     L.weights_materialize_pipelined.argtypes = [POINTER(kv_pool_desc), c_uint32, c_void_p, POINTER(wm_tensor), c_uint32,
                                                 c_uint64, c_void_p, c_void_p]
+    L.kv_compact_moves.restype = c_int
+    L.kv_compact_moves.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), c_uint32, c_uint32, c_void_p]
+    L.kv_movers_in_front.restype = c_uint32
+    L.kv_movers_in_front.argtypes = [c_void_p, c_uint32, c_uint32, c_uint32]
+    L.weights_materialize_front.restype = c_int
+    L.weights_materialize_front.argtypes = [POINTER(kv_pool_desc), c_uint32, c_uint64, POINTER(wm_tensor), c_uint32,
+                                            c_void_p, c_void_p, c_void_p]
     L.kv_switch.restype = c_int
     L.kv_switch.argtypes = [POINTER(kv_switch_request), POINTER(kv_plan_state)]
     L.kv_reserve_blocks.restype = c_int64
@@ -254,8 +262,26 @@ def weights_materialize_pipelined(pool: kv_pool_desc, boundary: int, live_host, 
                                                 _ptr(copy_stream), _ptr(compaction_done)))
 
 
+def kv_compact_moves(pool: kv_pool_desc, plan: kv_plan, first_move: int, max_moves: int, stream=0) -> None:
+    _check("kv_compact_moves", load().kv_compact_moves(byref(pool), byref(plan), first_move, max_moves, _ptr(stream)))
+
+
+def kv_movers_in_front(live_host, num_blocks: int, boundary: int, front_blocks: int) -> int:
+    live_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
+    return int(load().kv_movers_in_front(live_ptr, num_blocks, boundary, front_blocks))
+
+
+def weights_materialize_front(pool: kv_pool_desc, boundary: int, front_bytes: int, tensors, copy_stream=0,
+                              front_done=None, compaction_done=None) -> None:
+    arr, n = _tensor_array(tensors)
+    _check("weights_materialize_front",
+           load().weights_materialize_front(byref(pool), boundary, front_bytes, arr, n, _ptr(copy_stream),
+                                            _ptr(front_done), _ptr(compaction_done)))
+
+
 def kv_switch(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int, max_blocks_per_seq: int, tensors,
-              compute_stream, copy_stream, compaction_done, live_host=None, early_bytes: int = 0) -> kv_plan_state:
+              compute_stream, copy_stream, compaction_done, live_host=None, early_bytes: int = 0,
+              front_done=None) -> kv_plan_state:
     """The whole hand-over in one call; returns the plan's header.  Raises WarmKVError (KV_E_NOSPACE) if the
     request is infeasible, in which case nothing was moved or sent."""
     arr, n = _tensor_array(tensors)
@@ -264,7 +290,7 @@ def kv_switch(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int,
         live_host_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
     rq = kv_switch_request(ctypes.pointer(pool), ctypes.pointer(plan), _ptr(live_in), live_host_ptr, _ptr(tables),
                            num_seqs, max_blocks_per_seq, arr, n, 0, early_bytes, _ptr(compute_stream),
-                           _ptr(copy_stream), _ptr(compaction_done))
+                           _ptr(copy_stream), _ptr(compaction_done), _ptr(front_done))
     st = kv_plan_state()
     _check("kv_switch", load().kv_switch(byref(rq), byref(st)))
     return st

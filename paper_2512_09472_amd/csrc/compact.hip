@@ -65,7 +65,17 @@ struct CopyArgs {
   uint32_t chunks_per_seg;
   uint32_t units_per_move;  // segs * chunks_per_seg
   uint32_t seg_outer;       // unit order: 1 = segment-major (layer by layer), 0 = move-major
+  uint32_t move_first;      // this launch copies moves [move_first, move_first + move_count) of the plan;
+  uint32_t move_count;      // src and dst already point at entry move_first
 };
+
+// Moves of the plan that fall to a launch over [first, first + count).
+__device__ __forceinline__ uint32_t moves_of_launch(const kv_plan_state* state, uint32_t first, uint32_t count) {
+  if (state->status != KV_OK) return 0u;
+  const uint32_t n = state->n_moves;
+  if (n <= first) return 0u;
+  return n - first < count ? n - first : count;
+}
 
 // One unit of work, resolved: where to read, where to write, how much.
 struct Unit {
@@ -185,7 +195,7 @@ template <int UNROLL, bool NT, bool PREFETCH>
 __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a) {
   // No early return once tickets are drawn: every workgroup must draw its one
   // out-of-range ticket and sign out below, or the counters would not return to zero.
-  const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
+  const uint32_t n_moves = moves_of_launch(a.state, a.move_first, a.move_count);
   const uint32_t n_units = n_moves * a.units_per_move;  // host checked: fits 31 bits
   const uint32_t tid = threadIdx.x;
   __shared__ Unit s_unit[2];
@@ -247,11 +257,13 @@ struct PackArgs {
   uint32_t recip;        // ceil(2^32 / seg_vecs); v / seg_vecs == mulhi(v, recip) for v < 2^16 (unused if seg_vecs == 1)
   uint32_t pack;         // moves per ticket, 2..kMaxPack
   uint32_t ticket_vecs;  // pack * seg_vecs, in (ROWS-1)*256 .. ROWS*256
+  uint32_t move_first;   // as in CopyArgs
+  uint32_t move_count;
 };
 
 template <bool NT, int ROWS>
 __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a) {
-  const uint32_t n_moves = a.state->status == KV_OK ? a.state->n_moves : 0u;
+  const uint32_t n_moves = moves_of_launch(a.state, a.move_first, a.move_count);
   const uint32_t groups = (n_moves + a.pack - 1u) / a.pack;  // tickets per segment
   const uint32_t n_units = groups * a.segs;                  // host checked: fits 31 bits
   const uint32_t tid = threadIdx.x;
@@ -368,8 +380,10 @@ int launch(const CopyArgs& a, uint32_t workgroups, bool nt, bool prefetch, hipSt
 
 using namespace warmkv;
 
-extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
-                                 const kv_compact_tuning* tuning, void* stream) {
+namespace {
+
+int launch_copy(const kv_pool_desc* pool, const kv_plan* plan, const kv_compact_tuning* tuning,
+                uint32_t move_first, uint32_t move_count, void* stream) {
   if (pool == nullptr || plan == nullptr || plan->state == nullptr) return KV_E_NULL;
   if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
   if (!pool_extent_ok(*pool)) return KV_E_RANGE;  // zero or absurd sizes
@@ -390,6 +404,7 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
                       pool->layer_stride_bytes < (uint64_t)pool->num_blocks * pool->tile_bytes))
     return KV_E_RANGE;
   if (plan->capacity == 0 || pool->num_blocks == 0) return KV_OK;  // nothing can move
+  if (move_first >= plan->capacity || move_count == 0) return KV_OK;   // no such moves
   if (pool->base == nullptr || plan->src == nullptr || plan->dst == nullptr) return KV_E_NULL;
   if (((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
 
@@ -407,8 +422,10 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
   const uint64_t segs = layer_major ? pool->num_layers : 1u;
   const uint64_t chunks_per_seg = (a.seg_bytes + chunk - 1) / chunk;
   if (segs * chunks_per_seg * plan->capacity >= (1ull << 31)) return KV_E_RANGE;  // unit ids are 32-bit
-  a.src = plan->src;
-  a.dst = plan->dst;
+  a.src = plan->src + move_first;
+  a.dst = plan->dst + move_first;
+  a.move_first = move_first;
+  a.move_count = move_count;
   a.state = plan->state;
   a.num_blocks = plan->num_blocks;
   a.boundary = plan->boundary;
@@ -447,6 +464,8 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
     const uint32_t fit = ticket_bytes / (uint32_t)a.seg_bytes;
     p.pack = fit < kMaxPack ? fit : kMaxPack;
     p.ticket_vecs = p.pack * p.seg_vecs;
+    p.move_first = move_first;
+    p.move_count = move_count;
     switch ((p.ticket_vecs + kCopyThreads - 1u) / kCopyThreads) {  // rows of a whole ticket
       case 1: return launch_packed<1>(p, workgroups, nt, s);
       case 2: return launch_packed<2>(p, workgroups, nt, s);
@@ -476,6 +495,18 @@ extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
   }
 }
 
+}  // namespace
+
+extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
+                                 const kv_compact_tuning* tuning, void* stream) {
+  return launch_copy(pool, plan, tuning, 0u, ~0u, stream);
+}
+
 extern "C" int kv_compact(const kv_pool_desc* pool, const kv_plan* plan, void* stream) {
-  return kv_compact_launch(pool, plan, nullptr, stream);
+  return launch_copy(pool, plan, nullptr, 0u, ~0u, stream);
+}
+
+extern "C" int kv_compact_moves(const kv_pool_desc* pool, const kv_plan* plan, uint32_t first_move,
+                                uint32_t max_moves, void* stream) {
+  return launch_copy(pool, plan, nullptr, first_move, max_moves, stream);
 }

@@ -238,6 +238,56 @@ extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t 
   return requests.flush();
 }
 
+extern "C" uint32_t kv_movers_in_front(const uint64_t* live_host, uint32_t num_blocks, uint32_t boundary,
+                                       uint32_t front_blocks) {
+  if (live_host == nullptr || boundary >= num_blocks) return 0u;
+  const uint64_t end = std::min<uint64_t>(num_blocks, (uint64_t)boundary + front_blocks);
+  uint32_t n = 0;
+  for (uint64_t i = boundary; i < end; ++i) n += was_live(live_host, i) ? 1u : 0u;
+  return n;
+}
+
+// Front-first weight stream.  The block copy takes its moves in ascending
+// source order, so the reclaimed region becomes ready from its start: once the
+// movers of the first front_bytes have been read (front_done), every byte below
+// that mark may be written, while the rest of the block copy is still running.
+// Unlike the block-granular schedule this cuts each tensor at most once.
+extern "C" int weights_materialize_front(const kv_pool_desc* pool, uint32_t boundary, uint64_t front_bytes,
+                                         const wm_tensor* tensors, uint32_t n_tensors, void* copy_stream,
+                                         void* front_done, void* compaction_done) {
+  Region r;
+  int rc = validate(pool, boundary, tensors, n_tensors, &r);
+  if (rc != KV_OK) return rc;
+  if (r.layer_major) return KV_E_RANGE;
+  hipStream_t s = (hipStream_t)copy_stream;
+  uint8_t* region = (uint8_t*)pool->base + r.offset;
+  auto front_part = [&](const wm_tensor& t) -> uint64_t {  // leading bytes of t that lie below the mark
+    return t.dst_offset >= front_bytes ? 0 : std::min(t.bytes, front_bytes - t.dst_offset);
+  };
+  if (front_done != nullptr) {
+    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)front_done, 0));
+    if (rc != KV_OK) return rc;
+  }
+  Requests requests(s);
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    rc = requests.add(region + tensors[i].dst_offset, (const uint8_t*)tensors[i].host_ptr, front_part(tensors[i]));
+    if (rc != KV_OK) return rc;
+  }
+  rc = requests.flush();
+  if (rc != KV_OK) return rc;
+  if (compaction_done != nullptr) {
+    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+    if (rc != KV_OK) return rc;
+  }
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const uint64_t head = front_part(tensors[i]);
+    rc = requests.add(region + tensors[i].dst_offset + head, (const uint8_t*)tensors[i].host_ptr + head,
+                      tensors[i].bytes - head);
+    if (rc != KV_OK) return rc;
+  }
+  return requests.flush();
+}
+
 // The whole hand-over in one call.  The separate entry points leave one gap
 // to the caller: an infeasible plan turns kv_compact and kv_remap_tables into
 // no-ops, but a weight stream enqueued behind them would still overwrite the
@@ -266,13 +316,35 @@ extern "C" int kv_switch(const kv_switch_request* rq, kv_plan_state* result) {
   if (result != nullptr) *result = st;
   if (st.status != KV_OK) return st.status;  // running requests keep their blocks; no weight byte is sent
 
-  rc = kv_compact(pool, plan, rq->compute_stream);
+  const bool can_pipeline = rq->live_host != nullptr && !r.layer_major && r.block_bytes != 0;
+  const bool front_first = can_pipeline && rq->front_done != nullptr && rq->n_tensors != 0;
+  uint64_t front_bytes = 0;
+  if (front_first) {
+    // Enough weight bytes below the mark to keep the link busy until the block copy has ended:
+    // the link carries roughly 1/120 of what the block copy moves in the same time; twice that.
+    const uint64_t moved = 2ull * st.n_moves * r.block_bytes;
+    front_bytes = rq->early_bytes ? rq->early_bytes : std::max<uint64_t>(64ull << 20, moved / 64);
+    const uint64_t front_blocks =
+        std::min<uint64_t>((front_bytes + r.block_bytes - 1) / r.block_bytes, pool->num_blocks - plan->boundary);
+    front_bytes = front_blocks * r.block_bytes;
+    const uint32_t head = kv_movers_in_front(rq->live_host, pool->num_blocks, plan->boundary, (uint32_t)front_blocks);
+    rc = kv_compact_moves(pool, plan, 0u, head, rq->compute_stream);
+    if (rc != KV_OK) return rc;
+    rc = hip_rc(hipEventRecord((hipEvent_t)rq->front_done, (hipStream_t)rq->compute_stream));
+    if (rc != KV_OK) return rc;
+    rc = kv_compact_moves(pool, plan, head, ~0u, rq->compute_stream);
+  } else {
+    rc = kv_compact(pool, plan, rq->compute_stream);
+  }
   if (rc != KV_OK) return rc;
   rc = hip_rc(hipEventRecord((hipEvent_t)rq->compaction_done, (hipStream_t)rq->compute_stream));
   if (rc != KV_OK) return rc;
   rc = kv_remap_tables(rq->tables, rq->num_seqs, rq->max_blocks_per_seq, plan, rq->compute_stream);
   if (rc != KV_OK) return rc;
-  if (rq->live_host != nullptr && !r.layer_major && r.block_bytes != 0)
+  if (front_first)
+    return weights_materialize_front(pool, plan->boundary, front_bytes, rq->tensors, rq->n_tensors, rq->copy_stream,
+                                     rq->front_done, rq->compaction_done);
+  if (can_pipeline)
     return weights_materialize_pipelined(pool, plan->boundary, rq->live_host, rq->tensors, rq->n_tensors,
                                          rq->early_bytes, rq->copy_stream, rq->compaction_done);
   return weights_materialize(pool, plan->boundary, rq->tensors, rq->n_tensors, rq->copy_stream,

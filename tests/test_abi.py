@@ -6,6 +6,7 @@ import json
 import os
 import re
 
+import numpy as np
 import pytest
 
 import paper_2512_09472_amd as wk
@@ -37,7 +38,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.kv_compact_tuning) == 16
     assert ctypes.sizeof(binding.wm_tensor) == 24
     assert ctypes.sizeof(binding.wm_piece) == 32
-    assert ctypes.sizeof(binding.kv_switch_request) == 96
+    assert ctypes.sizeof(binding.kv_switch_request) == 104
 
 
 def test_workspace_and_bind():
@@ -281,3 +282,28 @@ def test_absurd_pool_sizes_are_refused():
         with pytest.raises(wk.WarmKVError) as e:
             wk.weights_materialize(pool, b, [(FAKE, 16, 0)])
         assert e.value.code == wk.KV_E_RANGE
+
+
+def test_movers_in_front_counts_live_blocks_above_the_boundary():
+    rs = np.random.default_rng(3)
+    for nb, b in ((1, 0), (64, 64), (130, 70), (1000, 333), (5000, 4999)):
+        bits = rs.random(nb) < 0.5
+        words = np.packbits(bits, bitorder="little")
+        words = np.concatenate([words, np.zeros((-len(words)) % 8, np.uint8)]).view(np.uint64)
+        for front in (0, 1, 7, 64, 65, nb, nb + 100):
+            assert wk.kv_movers_in_front(words, nb, b, front) == int(bits[b:b + front].sum()), (nb, b, front)
+
+
+def test_front_first_stream_validates_like_the_plain_one():
+    nb, b, tile = 64, 40, 4096
+    pool = wk.pool_desc(FAKE + (1 << 20), nb, 2, tile)
+    region = (nb - b) * 2 * tile
+    for tensors, code in (([(FAKE, region + 16, 0)], wk.KV_E_TOOBIG),
+                          ([(FAKE, 4096, 0), (FAKE, 4096, 4095)], wk.KV_E_OVERLAP),
+                          ([(None, 4096, 0)], wk.KV_E_NULL)):
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.weights_materialize_front(pool, b, 8192, tensors)
+        assert e.value.code == code
+    with pytest.raises(wk.WarmKVError) as e:      # layer-major pools: the region is L strips, there is no single front
+        wk.weights_materialize_front(wk.pool_desc(FAKE + (1 << 20), nb, 2, tile, nb * tile), b, 8192, [(FAKE, 16, 0)])
+    assert e.value.code == wk.KV_E_RANGE

@@ -559,7 +559,81 @@ def test_plan_can_be_reused_after_the_pool_changes(oracle):
     assert p3.n_moves == 3
 
 
-@pytest.mark.parametrize("pipelined", [False, True])
+@pytest.mark.parametrize("kv_heads", [8, 1])     # 128 KiB blocks: ticket kernel; 16 KiB blocks: several moves per ticket
+def test_block_copy_of_a_part_of_the_plan(oracle, kv_heads):
+    """kv_compact_moves over [first, first + max): exactly those moves, and the parts together
+    give the whole block copy."""
+    cfg = CONFIGS[1].scaled(num_blocks=1200, num_layers=2, num_seqs=60, kv_heads=kv_heads)
+    w = make_workload(cfg)
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    n = p.n_moves
+    assert n > 40
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    wk.kv_plan_reclaim(gh.to_dev(w.live), dp.plan)
+    for first, count in ((0, 17), (17, 1), (n - 5, 100), (n, 3), (5, 0), (3, n - 3), (cfg.num_blocks, 9)):
+        want = pool0.copy()
+        lo, hi = min(first, n), min(first + count, n)
+        part = oracle.Plan(0, p.src[lo:hi], p.dst[lo:hi], p.new_id, p.live_out, hi - lo, cfg.num_blocks, cfg.boundary)
+        oracle.compact(want, cfg.block_bytes, part)
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        wk.kv_compact_moves(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes), dp.plan, first, count)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want), (first, count)
+        st = dp.state()
+        assert st.ticket == 0 and st.finished == 0
+    want = pool0.copy()
+    oracle.compact(want, cfg.block_bytes, p)
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    for first, count in ((0, 9), (9, n // 2), (9 + n // 2, 1 << 31)):
+        wk.kv_compact_moves(pool, dp.plan, first, count)
+    torch.cuda.synchronize()
+    assert np.array_equal(pool_dev.cpu().numpy(), want)
+
+
+def test_front_first_weight_stream_matches_oracle(oracle):
+    """The front-first stream writes the same bytes as the plain one wherever the mark falls:
+    before every tensor, inside one, on a tensor boundary, beyond the region."""
+    cfg = CONFIGS[2].scaled(num_blocks=512, num_layers=2, num_seqs=48)
+    w = make_workload(cfg)
+    bb = cfg.block_bytes
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    region = (cfg.num_blocks - cfg.boundary) * bb
+    sizes = [3 * bb + 48, 4096, 9 * bb, region // 8 // 16 * 16]
+    offs = [16, 3 * bb + 64, 4 * bb, region - sizes[3]]
+    buf = torch.empty(sum(sizes), dtype=torch.uint8, pin_memory=True)
+    buf.numpy()[:] = content.item_bytes_host(0xF0, 0, -(-buf.numel() // 8) * 8, None)[:buf.numel()]
+    cuts = np.concatenate([[0], np.cumsum(sizes)])
+    views = [buf[int(cuts[i]):int(cuts[i + 1])] for i in range(len(sizes))]
+    tensors = [(v, v.numel(), o) for v, o in zip(views, offs)]
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want = pool0.copy()
+    oracle.compact(want, bb, p)
+    assert oracle.materialize(want, cfg.boundary * bb, [(v.numpy(), o) for v, o in zip(views, offs)]) == 0
+    for front_blocks in (0, 1, 3, 4, 13, cfg.num_blocks):
+        front_bytes = front_blocks * bb
+        head = wk.kv_movers_in_front(w.live, cfg.num_blocks, cfg.boundary, front_blocks)
+        assert head == int((p.src < cfg.boundary + front_blocks).sum())
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+        dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+        live_dev = gh.to_dev(w.live)
+        s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+        front_done, done = torch.cuda.Event(), torch.cuda.Event()
+        torch.cuda.synchronize()
+        wk.kv_plan_reclaim(live_dev, dp.plan, s_compute.cuda_stream)
+        wk.kv_compact_moves(pool, dp.plan, 0, head, s_compute.cuda_stream)
+        front_done.record(s_compute)
+        wk.kv_compact_moves(pool, dp.plan, head, 1 << 31, s_compute.cuda_stream)
+        done.record(s_compute)
+        wk.weights_materialize_front(pool, cfg.boundary, front_bytes, tensors, s_copy.cuda_stream,
+                                     front_done.cuda_event, done.cuda_event)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want), front_blocks
+
+
+@pytest.mark.parametrize("pipelined", [False, True, "front"])
 def test_switch_in_one_call(oracle, pipelined):
     """kv_switch = plan + block copy + table rewrite + weight stream; byte-identical to the
     oracle's steps.  An infeasible request comes back as KV_E_NOSPACE with no pool byte, table
@@ -589,11 +663,13 @@ def test_switch_in_one_call(oracle, pipelined):
     dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
     live_dev = gh.to_dev(w.live)
     s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
-    done = torch.cuda.Event()
+    done, front_done = torch.cuda.Event(), torch.cuda.Event()
     done.record(s_compute)                 # torch creates the HIP event lazily, on its first record
+    front_done.record(s_compute)
+    front = front_done.cuda_event if pipelined == "front" else None
     torch.cuda.synchronize()
     st = wk.kv_switch(pool, dp.plan, live_dev, tables_dev, *w.tables.shape, tensors, s_compute.cuda_stream,
-                      s_copy.cuda_stream, done.cuda_event, live_host=w.live if pipelined else None)
+                      s_copy.cuda_stream, done.cuda_event, live_host=w.live if pipelined else None, front_done=front)
     assert st.status == 0 and st.n_moves == p.n_moves
     torch.cuda.synchronize()
     _compare_plan(dp, p)
@@ -609,7 +685,7 @@ def test_switch_in_one_call(oracle, pipelined):
     tables_dev = torch.from_numpy(wf.tables).to(gh.dev())
     with pytest.raises(wk.WarmKVError) as e:
         wk.kv_switch(pool, dp.plan, gh.to_dev(wf.live), tables_dev, *wf.tables.shape, tensors, s_compute.cuda_stream,
-                     s_copy.cuda_stream, done.cuda_event, live_host=wf.live if pipelined else None)
+                     s_copy.cuda_stream, done.cuda_event, live_host=wf.live if pipelined else None, front_done=front)
     assert e.value.code == wk.KV_E_NOSPACE
     torch.cuda.synchronize()
     assert np.array_equal(pool_dev.cpu().numpy(), pool0), "an infeasible hand-over must not write the pool"

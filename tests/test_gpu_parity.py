@@ -848,14 +848,17 @@ def test_plain_c_client_of_the_abi(tmp_path):
 
 
 def test_randomized_reclaims_against_the_oracle(oracle):
-    """Forty seeded random pools: sizes, odd tile sizes, layouts, occupancies, boundaries and
-    launch shapes drawn at random; plan, tables and every pool byte compared with the oracle."""
+    """Seventy seeded random pools: sizes, odd tile sizes (small ones that share tickets, large
+    ones with ragged tails), layouts, occupancies, boundaries and launch shapes drawn at random,
+    the block copy in one launch or in three parts; plan, tables and every pool byte compared
+    with the oracle."""
     rs = np.random.default_rng(20251209)
-    for case in range(40):
-        nb = int(rs.integers(1, 3000))
+    for case in range(70):
+        big_tile = case % 3 == 2
+        nb = int(rs.integers(1, 300 if big_tile else 3000))
         b = int(rs.integers(0, nb + 1))
         layers = int(rs.integers(1, 7))
-        tile = 16 * int(rs.integers(1, 600))
+        tile = 16 * int(rs.integers(600, 12000) if big_tile else rs.integers(1, 600))
         layer_major = bool(rs.integers(0, 2))
         pad = 256 * int(rs.integers(0, 4)) if layer_major else 0
         stride = -(-(nb * tile) // 256) * 256 + pad if layer_major else 0
@@ -876,16 +879,25 @@ def test_randomized_reclaims_against_the_oracle(oracle):
             oracle.compact(want_pool, layers * tile, p)
         bad = oracle.remap(want_tables, p)
         tuning = dict(workgroups=int(rs.choice([0, 1, 3, 64, 256, 1000])), chunk_bytes=4096 * int(rs.integers(1, 40)),
-                      flags=(int(rs.choice([2, 4, 8, 16, 32])) << 4) | int(rs.integers(0, 8)))
+                      flags=(int(rs.choice([2, 4, 8, 16, 32])) << 4) | int(rs.integers(0, 16)))
+        parts = None
+        if case % 2 == 1:                      # default launch shape, block copy in three parts
+            cut = sorted(int(x) for x in rs.integers(0, max(1, p.n_moves) + 2, size=2))
+            parts = [(0, cut[0]), (cut[0], cut[1] - cut[0]), (cut[1], 1 << 31)]
+            tuning = None
         _say(f"[random {case}] NB={nb} b={b} L={layers} tile={tile} layer_major={layer_major} stride={stride} "
-             f"status={p.status} n={p.n_moves} tuning={tuning}")
+             f"status={p.status} n={p.n_moves} tuning={tuning} parts={parts}")
         pool_dev = torch.from_numpy(pool0).to(gh.dev())
         pool = wk.pool_desc(pool_dev, nb, layers, tile, stride)
         dp = gh.DevicePlan(nb, b)
         tables_dev = torch.from_numpy(tables).to(gh.dev())
         live_dev = gh.to_dev(live)
         wk.kv_plan_reclaim(live_dev, dp.plan)
-        wk.kv_compact_launch(pool, dp.plan, **tuning)
+        if parts is None:
+            wk.kv_compact_launch(pool, dp.plan, **tuning)
+        else:
+            for first, count in parts:
+                wk.kv_compact_moves(pool, dp.plan, first, count)
         wk.kv_remap_tables(tables_dev, rows, cols, dp.plan)
         torch.cuda.synchronize()
         st = _compare_plan(dp, p)

@@ -207,7 +207,10 @@ __device__ __forceinline__ void copy_bytes(const u32x4* __restrict__ sp, u32x4* 
 // LDS.  Drawing ahead hides the atomic and the two id loads, yet measured 4 %
 // slower on every workload: the short pause between units keeps fewer bytes in
 // flight per compute unit, and the memory system is saturated either way.
-template <int UNROLL, bool NT, bool PREFETCH>
+// WHOLE: every unit is exactly one step of UNROLL rows (segments that are a
+// whole number of units: the benchmark pools); the copy is then that one step
+// and nothing else, with no code for ragged ends anywhere near it.
+template <int UNROLL, bool NT, bool PREFETCH, bool WHOLE>
 __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a) {
   // No early return once tickets are drawn: every workgroup must draw its one
   // out-of-range ticket and sign out below, or the counters would not return to zero.
@@ -226,7 +229,11 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
     const uint64_t dst_off = uniform64(s_unit[slot].dst_off);
     // The other slot was last read before the previous barrier: free to refill.
     if (PREFETCH && tid == 0) s_unit[slot ^ 1u] = resolve_unit(a, next_ticket(a.state, n_units), n_moves, n_units);
-    copy_bytes<UNROLL, NT>((const u32x4*)(a.base + src_off), (u32x4*)(a.base + dst_off), len, tid);
+    if (WHOLE) {
+      if (len != 0) copy_rows<UNROLL, NT>((const u32x4*)(a.base + src_off), (u32x4*)(a.base + dst_off), tid);
+    } else {
+      copy_bytes<UNROLL, NT>((const u32x4*)(a.base + src_off), (u32x4*)(a.base + dst_off), len, tid);
+    }
     if (!PREFETCH) {
       __syncthreads();
       if (tid == 0) s_unit[slot ^ 1u] = resolve_unit(a, next_ticket(a.state, n_units), n_moves, n_units);
@@ -381,14 +388,21 @@ int launch_packed(const PackArgs& p, uint32_t workgroups, bool nt, hipStream_t s
   return launch_rc();
 }
 
+template <int UNROLL, bool WHOLE>
+int launch_shape(const CopyArgs& a, uint32_t workgroups, bool nt, bool prefetch, hipStream_t s) {
+  const dim3 grid(workgroups), block(kCopyThreads);
+  if (nt && prefetch) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, true, true, WHOLE>), grid, block, 0, s, a);
+  else if (nt) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, true, false, WHOLE>), grid, block, 0, s, a);
+  else if (prefetch) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, false, true, WHOLE>), grid, block, 0, s, a);
+  else hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, false, false, WHOLE>), grid, block, 0, s, a);
+  return launch_rc();
+}
+
 template <int UNROLL>
 int launch(const CopyArgs& a, uint32_t workgroups, bool nt, bool prefetch, hipStream_t s) {
-  const dim3 grid(workgroups), block(kCopyThreads);
-  if (nt && prefetch) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, true, true>), grid, block, 0, s, a);
-  else if (nt) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, true, false>), grid, block, 0, s, a);
-  else if (prefetch) hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, false, true>), grid, block, 0, s, a);
-  else hipLaunchKernelGGL((compact_ticket_kernel<UNROLL, false, false>), grid, block, 0, s, a);
-  return launch_rc();
+  const bool whole = a.chunk_bytes == (uint32_t)UNROLL * kRowBytes && a.seg_bytes % a.chunk_bytes == 0;
+  return whole ? launch_shape<UNROLL, true>(a, workgroups, nt, prefetch, s)
+               : launch_shape<UNROLL, false>(a, workgroups, nt, prefetch, s);
 }
 
 }  // namespace

@@ -140,6 +140,33 @@ def test_planner_matches_oracle(oracle, nb, b, p_live):
         assert st.n_free_below == free_below
 
 
+def test_degenerate_pools(oracle):
+    """No blocks at all, nothing live, everything below the boundary live, boundary 0 or NB:
+    plan, block copy and table rewrite all run, move nothing and report n_moves = 0."""
+    tile = 4096
+    for nb, b, ids in ((0, 0, []), (1, 1, []), (70, 0, []), (70, 70, list(range(70))), (70, 35, list(range(35))),
+                       (70, 35, []), (129, 64, [0, 63]), (64, 0, [])):
+        live = bitmap_from_ids(np.array(ids, dtype=np.int64), nb)
+        p = oracle.plan(live, nb, b)
+        assert p.status == 0 and p.n_moves == 0
+        _say(f"[degenerate] NB={nb} b={b} live={len(ids)}")
+        pool0 = np.random.default_rng(nb + b).integers(0, 256, max(nb, 1) * tile, dtype=np.uint8)
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        tables = np.array([ids[:4] + [-1] * (4 - len(ids[:4]))], dtype=np.int32)
+        tables_dev = torch.from_numpy(tables).to(gh.dev())
+        dp = gh.DevicePlan(nb, b)
+        live_dev = gh.to_dev(live) if live.size else None
+        wk.kv_plan_reclaim(live_dev, dp.plan)
+        wk.kv_compact(wk.pool_desc(pool_dev, nb, 1, tile), dp.plan)
+        wk.kv_compact_moves(wk.pool_desc(pool_dev, nb, 1, tile), dp.plan, 0, 5)
+        wk.kv_remap_tables(tables_dev, 1, 4, dp.plan)
+        torch.cuda.synchronize()
+        st = _compare_plan(dp, p) if nb else dp.state()
+        assert st.status == 0 and st.n_moves == 0 and st.n_bad_entries == 0 and st.ticket == 0 and st.finished == 0
+        assert np.array_equal(pool_dev.cpu().numpy(), pool0)
+        assert np.array_equal(tables_dev.cpu().numpy(), tables)
+
+
 def test_planner_on_handworked_fixtures():
     import json
     import os

@@ -18,7 +18,7 @@
 namespace warmkv {
 namespace {
 
-constexpr uint64_t kChunkBytes = 1ull << 30;     // bound on one DMA request
+constexpr uint64_t kChunkBytes = 4ull << 30;     // bound on one DMA request (each boundary idles the link ~30 us)
 constexpr uint64_t kDefaultEarly = 128ull << 20;  // early bytes when the caller passes 0: about what the link
                                                  // carries during a few ms of block copy; every piece
                                                  // costs ~10 us of request overhead, so more loses

@@ -307,3 +307,24 @@ def test_front_first_stream_validates_like_the_plain_one():
     with pytest.raises(wk.WarmKVError) as e:      # layer-major pools: the region is L strips, there is no single front
         wk.weights_materialize_front(wk.pool_desc(FAKE + (1 << 20), nb, 2, tile, nb * tile), b, 8192, [(FAKE, 16, 0)])
     assert e.value.code == wk.KV_E_RANGE
+
+
+def test_host_code_under_sanitizers(tmp_path):
+    """The library's host arithmetic (schedules, validation, Eq. 4, the reverse switch, the
+    control-plane formulas) built with ASan + UBSan on the host side and driven by a C++ program
+    with exact-size buffers.  Nothing in it reaches a HIP call."""
+    import glob
+    import subprocess
+    from paper_2512_09472_amd import build as lib_build
+    exe = str(tmp_path / "host_san")
+    srcs = [f for f in sorted(glob.glob(os.path.join(lib_build.CSRC, "*.hip"))) if not f.endswith("vmm.hip")]
+    cmd = ["hipcc", "--offload-arch=gfx950", "-O1", "-g", "-std=c++17",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+           "-Xarch_host", "-fno-sanitize-recover=undefined",
+           "-I", lib_build.INCLUDE, "-I", lib_build.CSRC, os.path.join(ROOT, "tests", "host_san_driver.cpp"), *srcs,
+           "-o", exe]
+    subprocess.run(cmd, check=True, capture_output=True, timeout=600)
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=300,
+                       env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))      # the HIP runtime keeps its own allocations
+    assert r.returncode == 0 and "ok" in r.stdout, (r.stdout + r.stderr)[-3000:]

@@ -49,6 +49,7 @@ SCALED = {
     # blocks of half a ticket or less: several moves share one ticket of the block copy
     "one_layer_16k_blocks": CONFIGS[1].scaled(num_blocks=3000, num_layers=1, kv_heads=2, num_seqs=60),
     "one_layer_7680_blocks": CONFIGS[1].scaled(num_blocks=2500, num_layers=1, kv_heads=3, head_dim=40, num_seqs=50),
+    "one_layer_40k_blocks": CONFIGS[1].scaled(num_blocks=1500, num_layers=1, kv_heads=5, num_seqs=50),   # two to a ticket of 20 rows
     "two_layer_288_blocks": CONFIGS[4].scaled(num_blocks=5000, num_layers=2, block_size=1, kv_heads=1, head_dim=72, len_hi=16, num_seqs=900),
     # more than 65 536 blocks: the planner's several-workgroup shape plus its join kernel feed the copy
     "many_small_blocks": CONFIGS[4].scaled(num_blocks=150_000, num_layers=2, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=6000),

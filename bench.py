@@ -62,6 +62,9 @@ def parse_args():
     ap.add_argument("--kv-heads", type=int, default=0,
                     help="override the config's KV heads per block (a tensor-parallel share has fewer: smaller "
                          "tiles, same block count); 0 = as the config says")
+    ap.add_argument("--size-sweep", action="store_true",
+                    help="instead of the benchmark: time the block copy alone on one-layer pools of 8 GiB whose "
+                         "block size runs from 256 B to 5 MiB (45 %% live, half reclaimed) and print one line per size")
     ap.add_argument("--vmm-compare", type=int, default=0, metavar="BLOCKS",
                     help="also time the no-move variant (HIP virtual-memory remapping of unused blocks' pages) on a "
                          "pool of this many blocks of the config's shape; 20480 = the full 8B-shaped pool, which "
@@ -124,12 +127,70 @@ def cpu_baseline(cfg, w, sample_moves: int):
                    "remap": round(t_remap * 1e3, 3)}}
 
 
+SWEEP_SIZES = [256, 512, 1040, 2048, 3072, 4096, 6144, 8192, 12288, 16384, 20480, 24576, 28672, 32768, 36864, 40960,
+               45056, 49152, 53248, 57344, 61440, 65536, 69632, 73728, 77824, 86016, 94208, 102400, 114688, 131072,
+               147456, 180224, 196608, 262144, 278528, 327680, 393216, 458752, 524288, 1048576 + 4096, 2097152, 5242880]
+
+
+def size_sweep(args):
+    """Block copy alone across block sizes (which kernel shape each size gets is the library's choice)."""
+    import torch
+    import paper_2512_09472_amd as wk
+    from synth import content
+    wk.binding.load()
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    s = stream.cuda_stream
+    rows = []
+    for tile in SWEEP_SIZES:
+        nb = min(1 << 22, max(2048, (8 << 30) // tile))
+        b = nb // 2
+        bits = np.random.default_rng(nb).random(nb) < 0.45
+        words = np.packbits(bits, bitorder="little")
+        words = np.concatenate([words, np.zeros((-len(words)) % 8, np.uint8)]).view(np.int64)
+        live_d = torch.from_numpy(words).to(dev)
+        pool_t = torch.empty(nb * tile, dtype=torch.uint8, device=dev)
+        content.fill_device(pool_t.data_ptr(), nb, tile, 1)
+        n_ws = wk.kv_plan_workspace_bytes(nb, b)
+        ws = torch.zeros(n_ws, dtype=torch.uint8, device=dev)
+        plan = wk.kv_plan_bind(ws, n_ws, nb, b)
+        pool = wk.pool_desc(pool_t, nb, 1, tile)
+        torch.cuda.synchronize()
+        wk.kv_plan_reclaim(live_d, plan, s)
+        n_moves = wk.kv_plan_fetch(plan, s).n_moves
+        tuning = dict(workgroups=args.workgroups, chunk_bytes=args.chunk_bytes, flags=args.flags)
+        for _ in range(2):
+            wk.kv_compact_launch(pool, plan, s, **tuning)
+        ms = []
+        for _ in range(7):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            wk.kv_compact_launch(pool, plan, s, **tuning)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms.append(e0.elapsed_time(e1))
+        st = wk.kv_plan_fetch(plan, s)
+        assert st.status == wk.KV_OK and st.ticket == 0 and st.finished == 0
+        gbps = 2 * n_moves * tile / min(ms) / 1e6
+        rows.append({"block_bytes": tile, "blocks": nb, "moved": n_moves, "kernel_ms_min": round(min(ms), 4),
+                     "GBps_rw": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBPS, 4)})
+        print(f"block {tile:>8} B x {nb:>8} blocks, {n_moves:>7} moved: {min(ms):.3f} ms  {gbps:7.0f} GB/s r+w  "
+              f"{100 * gbps / HBM_PEAK_GBPS:.1f} % of peak", file=sys.stderr, flush=True)
+        del pool_t
+    print(json.dumps({"metric": "block copy GB/s (read+write) by block size", "unit": "GB/s", "n_gpus": 1,
+                      "data": "synthetic", "peak": HBM_PEAK_GBPS, "sizes": rows}))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
         print(f"bench.py: this build runs on one GPU only (got --gpus {args.gpus}); "
               "there is no multi-GPU path to measure. Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+
+    if args.size_sweep:
+        size_sweep(args)
+        return
 
     import torch
     import paper_2512_09472_amd as wk

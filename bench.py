@@ -273,7 +273,7 @@ def main():
     reclaimed_bytes = (cfg.num_blocks - cfg.boundary) * bb
     # which block-copy kernel the library picked: units of half a ticket or less share tickets
     unit_bytes = cfg.tile_bytes if args.layout == "layer" else bb
-    ticket_bytes = min(args.chunk_bytes or 65536, 65536)
+    ticket_bytes = min(args.chunk_bytes, 65536) if args.chunk_bytes else 86016   # pairs of up to 42 KiB by default
     copy_kernel = ("compact_packed_kernel" if 2 * unit_bytes <= ticket_bytes and not args.flags & 8
                    else "compact_ticket_kernel")
     out = {

@@ -37,6 +37,7 @@ constexpr uint32_t kVecBytes = 16;
 constexpr uint32_t kRowBytes = kCopyThreads * kVecBytes;  // 4 KiB per workgroup per instruction
 constexpr uint32_t kDefaultChunk = 65536;
 constexpr uint32_t kDefaultUnroll = 16;                   // 16 rows = one whole 64 KiB unit per step
+constexpr uint32_t kMaxBurstRows = 21;                    // most rows one burst may have (register budget)
 
 template <bool NT>
 __device__ __forceinline__ u32x4 load16(const u32x4* p) {
@@ -165,6 +166,14 @@ __device__ __forceinline__ void copy_rows(const u32x4* __restrict__ sp, u32x4* _
   for (int j = 0; j < ROWS; ++j) store16<NT>(dp + i + j * kCopyThreads, v[j]);
 }
 
+// copy_rows<rows> for a run-time (uniform) row count in 1..MAX.
+template <int MAX, bool NT>
+__device__ __forceinline__ void copy_rows_of(const u32x4* __restrict__ sp, u32x4* __restrict__ dp, uint32_t i,
+                                             uint32_t rows) {
+  if (rows == (uint32_t)MAX) copy_rows<MAX, NT>(sp, dp, i);
+  else if constexpr (MAX > 1) copy_rows_of<MAX - 1, NT>(sp, dp, i, rows);
+}
+
 // Copy len bytes (multiple of 16) in steps of UNROLL rows; with the default
 // shape one step is the whole unit.  A shorter rest (the ragged end of a block
 // or tile that is not a whole number of units) goes out as one more burst of
@@ -176,14 +185,8 @@ __device__ __forceinline__ void copy_bytes(const u32x4* __restrict__ sp, u32x4* 
   uint32_t rows = len / kRowBytes;           // whole rows left
   // A unit of 17 to 21 rows (a 68-84 KiB tile kept in one unit) goes out as one burst too:
   // two segments of 36 KiB in one 18-row burst measured 2.5 % faster than 16 rows and 2.
-  if (UNROLL == 16 && rows > 16u && rows <= 21u) {
-    switch (rows) {
-      case 17: copy_rows<17, NT>(sp, dp, i); break;
-      case 18: copy_rows<18, NT>(sp, dp, i); break;
-      case 19: copy_rows<19, NT>(sp, dp, i); break;
-      case 20: copy_rows<20, NT>(sp, dp, i); break;
-      default: copy_rows<21, NT>(sp, dp, i); break;
-    }
+  if (UNROLL == 16 && rows > 16u && rows <= kMaxBurstRows) {
+    copy_rows_of<kMaxBurstRows, NT>(sp, dp, i, rows);
     i += rows * kCopyThreads;
     rows = 0;
   }
@@ -192,24 +195,7 @@ __device__ __forceinline__ void copy_bytes(const u32x4* __restrict__ sp, u32x4* 
   if (rows >= (uint32_t)UNROLL) { copy_rows<UNROLL, NT>(sp, dp, i); rows -= UNROLL; i += UNROLL * kCopyThreads; }
   for (; rows >= (uint32_t)UNROLL; rows -= UNROLL, i += UNROLL * kCopyThreads) copy_rows<UNROLL, NT>(sp, dp, i);
   if (UNROLL > 16 && rows >= 16u) { copy_rows<16, NT>(sp, dp, i); rows -= 16u; i += 16u * kCopyThreads; }
-  switch (rows) {  // uniform; one read burst and one write burst whatever the count
-    case 15: copy_rows<15, NT>(sp, dp, i); break;
-    case 14: copy_rows<14, NT>(sp, dp, i); break;
-    case 13: copy_rows<13, NT>(sp, dp, i); break;
-    case 12: copy_rows<12, NT>(sp, dp, i); break;
-    case 11: copy_rows<11, NT>(sp, dp, i); break;
-    case 10: copy_rows<10, NT>(sp, dp, i); break;
-    case 9: copy_rows<9, NT>(sp, dp, i); break;
-    case 8: copy_rows<8, NT>(sp, dp, i); break;
-    case 7: copy_rows<7, NT>(sp, dp, i); break;
-    case 6: copy_rows<6, NT>(sp, dp, i); break;
-    case 5: copy_rows<5, NT>(sp, dp, i); break;
-    case 4: copy_rows<4, NT>(sp, dp, i); break;
-    case 3: copy_rows<3, NT>(sp, dp, i); break;
-    case 2: copy_rows<2, NT>(sp, dp, i); break;
-    case 1: copy_rows<1, NT>(sp, dp, i); break;
-    default: break;
-  }
+  if (rows != 0) copy_rows_of<15, NT>(sp, dp, i, rows);  // one read burst and one write burst whatever the count
   i += rows * kCopyThreads;
   if (i < len / kVecBytes) store16<NT>(dp + i, load16<NT>(sp + i));  // partial last row
 }
@@ -277,8 +263,8 @@ __global__ __launch_bounds__(kCopyThreads) void compact_ticket_kernel(CopyArgs a
 // harmless) instead of being masked off.
 constexpr uint32_t kMaxPack = 256;   // moves per ticket: what one LDS table holds
 constexpr uint32_t kPackRows = 16;   // 128-bit accesses per lane per ticket (64 KiB per workgroup) ...
-constexpr uint32_t kPairRows = 21;   // ... but two segments of 32-42 KiB share a ticket of up to 84 KiB: one such
-                                     // segment per ticket is drawn faster than the counter hands tickets out
+                                     // ... but two segments of 32-42 KiB share a ticket of up to kMaxBurstRows rows:
+                                     // one such segment per ticket is drawn faster than the counter hands tickets out
 constexpr uint64_t kSkip = ~0ull;    // LDS marker of a move that failed the src >= boundary > dst check
 
 struct PackArgs {
@@ -395,12 +381,17 @@ __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a
   if (tid == 0) sign_out(a.state, n_units);
 }
 
-template <int ROWS>
-int launch_packed(const PackArgs& p, uint32_t workgroups, bool nt, hipStream_t s) {
-  const dim3 grid(workgroups), block(kCopyThreads);
-  if (nt) hipLaunchKernelGGL((compact_packed_kernel<true, ROWS>), grid, block, 0, s, p);
-  else hipLaunchKernelGGL((compact_packed_kernel<false, ROWS>), grid, block, 0, s, p);
-  return launch_rc();
+// Launch compact_packed_kernel<NT, rows> for a run-time row count in 1..MAX.
+template <int MAX>
+int launch_packed(const PackArgs& p, uint32_t rows, uint32_t workgroups, bool nt, hipStream_t s) {
+  if (rows == (uint32_t)MAX || MAX == 1) {
+    const dim3 grid(workgroups), block(kCopyThreads);
+    if (nt) hipLaunchKernelGGL((compact_packed_kernel<true, MAX>), grid, block, 0, s, p);
+    else hipLaunchKernelGGL((compact_packed_kernel<false, MAX>), grid, block, 0, s, p);
+    return launch_rc();
+  }
+  if constexpr (MAX > 1) return launch_packed<MAX - 1>(p, rows, workgroups, nt, s);
+  return KV_E_RANGE;
 }
 
 template <int UNROLL, bool WHOLE>
@@ -512,8 +503,8 @@ int launch_copy(const kv_pool_desc* pool, const kv_plan* plan, const kv_compact_
   // Segments of half a ticket or less: several moves per ticket.
   uint32_t ticket_bytes = chunk < kPackRows * kRowBytes ? chunk : kPackRows * kRowBytes;
   if ((tuning == nullptr || tuning->chunk_bytes == 0) && a.seg_bytes * 2u > ticket_bytes &&
-      a.seg_bytes * 2u <= kPairRows * kRowBytes)
-    ticket_bytes = kPairRows * kRowBytes;  // 40 KiB blocks: 6.05 -> 6.3 TB/s
+      a.seg_bytes * 2u <= kMaxBurstRows * kRowBytes)
+    ticket_bytes = kMaxBurstRows * kRowBytes;  // 40 KiB blocks: 6.05 -> 6.3 TB/s
   if ((flags & 8u) == 0 && a.seg_bytes * 2u <= ticket_bytes) {
     PackArgs p;
     p.base = a.base;
@@ -532,29 +523,7 @@ int launch_copy(const kv_pool_desc* pool, const kv_plan* plan, const kv_compact_
     p.ticket_vecs = p.pack * p.seg_vecs;
     p.move_first = move_first;
     p.move_count = move_count;
-    switch ((p.ticket_vecs + kCopyThreads - 1u) / kCopyThreads) {  // rows of a whole ticket
-      case 1: return launch_packed<1>(p, workgroups, nt, s);
-      case 2: return launch_packed<2>(p, workgroups, nt, s);
-      case 3: return launch_packed<3>(p, workgroups, nt, s);
-      case 4: return launch_packed<4>(p, workgroups, nt, s);
-      case 5: return launch_packed<5>(p, workgroups, nt, s);
-      case 6: return launch_packed<6>(p, workgroups, nt, s);
-      case 7: return launch_packed<7>(p, workgroups, nt, s);
-      case 8: return launch_packed<8>(p, workgroups, nt, s);
-      case 9: return launch_packed<9>(p, workgroups, nt, s);
-      case 10: return launch_packed<10>(p, workgroups, nt, s);
-      case 11: return launch_packed<11>(p, workgroups, nt, s);
-      case 12: return launch_packed<12>(p, workgroups, nt, s);
-      case 13: return launch_packed<13>(p, workgroups, nt, s);
-      case 14: return launch_packed<14>(p, workgroups, nt, s);
-      case 15: return launch_packed<15>(p, workgroups, nt, s);
-      case 16: return launch_packed<16>(p, workgroups, nt, s);
-      case 17: return launch_packed<17>(p, workgroups, nt, s);
-      case 18: return launch_packed<18>(p, workgroups, nt, s);
-      case 19: return launch_packed<19>(p, workgroups, nt, s);
-      case 20: return launch_packed<20>(p, workgroups, nt, s);
-      default: return launch_packed<21>(p, workgroups, nt, s);
-    }
+    return launch_packed<kMaxBurstRows>(p, (p.ticket_vecs + kCopyThreads - 1u) / kCopyThreads, workgroups, nt, s);
   }
 
   switch (unroll) {

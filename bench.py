@@ -37,7 +37,7 @@ LINK_PEAK_GBPS = 63.0           # PCIe 5.0 x16, one direction, theoretical
 # WRITE_SIZE, each scaled by what the counter shows for a plain 1 GiB copy: x2.0 and x1.0), for
 # configs[1], [3] and [4] with the default launch shape.  Profiler figures cannot be taken
 # inside this process; other workloads or launch shapes report null.
-MEASURED_TRAFFIC_BYTES = {(1, 4687): 19_671_032_946, (3, 3415): 35_828_946_669, (4, 15425): 32_367_484_279}
+MEASURED_TRAFFIC_BYTES = {(1, 4687): 19_668_999_326, (3, 3415): 35_828_382_869, (4, 15425): 32_366_820_165}
 
 
 def parse_args():

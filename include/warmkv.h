@@ -79,13 +79,17 @@ typedef struct kv_pool_desc {
 
 /* Device-resident result header of a plan (32 bytes). */
 typedef struct kv_plan_state {
-  int32_t  status;         /* KV_OK, KV_E_NOSPACE or KV_E_BADPLAN                        */
+  int32_t  status;         /* the planner's verdict: KV_OK or KV_E_NOSPACE; as returned by
+                              kv_plan_fetch also KV_E_BADPLAN (see bad_plan)             */
   uint32_t n_moves;        /* number of blocks to move (0 unless status == KV_OK)        */
   uint32_t n_free_below;   /* free ids below the boundary before the move                */
   uint32_t n_bad_entries;  /* table entries kv_remap_tables left alone (see there)       */
   uint32_t ticket;         /* kv_compact's work counter; zero between calls              */
   uint32_t finished;       /* kv_compact's exit counter; zero between calls              */
-  uint32_t reserved[2];
+  uint32_t bad_plan;       /* set to 1 by kv_compact when it skipped a move (see there);
+                              never changes `status` on the device, so that every
+                              workgroup of a launch sees the same plan                   */
+  uint32_t reserved;
 } kv_plan_state;
 
 /* A relocation plan.  All pointers are [device] and point into the workspace
@@ -124,12 +128,16 @@ int kv_plan_bind(kv_plan* plan, void* workspace, size_t workspace_bytes,
 int kv_plan_reclaim(const uint64_t* live_in, const kv_plan* plan, void* stream);
 
 /* Block copy: for k < n_moves, block dst[k] <- block src[k] (block_bytes each;
- * in a layer-major pool, tile by tile in every layer slab).
+ * in a layer-major pool, tile by tile in every layer slab).  This is what makes
+ * the unused space one byte range for the new model (it stands where the paper
+ * maps the pages of unused blocks into the prewarm slot: App. C, Fig. 4b step 2).
  * Source blocks keep their bytes; no byte at or above block `boundary` and no
  * byte of a non-destination block is written.  Does nothing unless
  * state.status == KV_OK.  A move with src < boundary, src >= NB or dst >=
  * boundary (possible only in a hand-built plan) is skipped and sets
- * state.status = KV_E_BADPLAN.  pool->num_blocks must equal plan->num_blocks.
+ * state.bad_plan = 1; every other move is still copied.  kv_plan_fetch then
+ * reports KV_E_BADPLAN and kv_remap_tables does nothing.
+ * pool->num_blocks must equal plan->num_blocks.
  * Uses state.ticket / state.finished as scratch counters (zeroed by the
  * planner, left at zero on exit): two kv_compact calls on one plan must not
  * overlap in time. */
@@ -160,12 +168,14 @@ int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
  * row-major, -1 = empty] becomes new_id[e].  Entries that name an id >= NB or
  * a block that was not live are left as they are and counted in
  * state.n_bad_entries (added to what is there).  Does nothing unless
- * state.status == KV_OK.  (The engine goes on seeing one address space and
+ * state.status == KV_OK and state.bad_plan == 0.  (The engine goes on seeing one address space and
  * never learns that blocks moved: App. C.) */
 int kv_remap_tables(int32_t* tables, uint32_t num_seqs, uint32_t max_blocks_per_seq,
                     const kv_plan* plan, void* stream);
 
-/* Synchronise `stream` and copy the plan's header to `out` [host]. */
+/* Synchronise `stream` and copy the plan's header to `out` [host];
+ * out->status is KV_E_BADPLAN if the planner said KV_OK and kv_compact has
+ * since skipped a move (state.bad_plan). */
 int kv_plan_fetch(const kv_plan* plan, void* stream, kv_plan_state* out);
 
 /* One weight tensor: `bytes` bytes at host_ptr [host, pinned] go to byte
@@ -429,6 +439,11 @@ int ws_place_replicas(const ws_model* models, uint32_t n_models,
 
 /* Library version, "major.minor". */
 const char* warmkv_version(void);
+
+/* Identifier of the source text this binary was compiled from (a hash over the
+ * HIP sources and headers, baked in by the build).  A loader that has the
+ * sources can tell a stale binary from a current one. */
+const char* warmkv_build_id(void);
 
 #ifdef __cplusplus
 }

@@ -11,6 +11,8 @@ from __future__ import annotations
 
 import ctypes
 import os
+import re
+import sys
 from ctypes import POINTER, Structure, byref, c_char_p, c_int, c_int32, c_int64, c_size_t, c_uint32, c_uint64, c_void_p
 
 from . import build as _build
@@ -34,7 +36,7 @@ EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_com
            "weights_materialize_pipelined", "kv_compact_moves", "kv_movers_in_front", "weights_materialize_front",
            "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
-           "ws_place_replicas", "warmkv_version")
+           "ws_place_replicas", "warmkv_version", "warmkv_build_id")
 
 
 class WarmKVError(RuntimeError):
@@ -50,7 +52,7 @@ class kv_pool_desc(Structure):
 
 class kv_plan_state(Structure):
     _fields_ = [("status", c_int32), ("n_moves", c_uint32), ("n_free_below", c_uint32), ("n_bad_entries", c_uint32),
-                ("ticket", c_uint32), ("finished", c_uint32), ("reserved", c_uint32 * 2)]
+                ("ticket", c_uint32), ("finished", c_uint32), ("bad_plan", c_uint32), ("reserved", c_uint32)]
 
 
 class kv_plan(Structure):
@@ -98,14 +100,43 @@ def library_path() -> str:
     return _build.LIB_PATH
 
 
+class StaleLibraryError(RuntimeError):
+    pass
+
+
+def _built_id(path: str) -> str | None:
+    """Build identifier of the library file at `path`, read from its bytes without loading it
+    (a stale library must not enter the process); None if there is no file or no identifier."""
+    if not os.path.exists(path):
+        return None
+    with open(path, "rb") as f:
+        m = re.search(rb"WARMKV_BUILD_ID=([0-9a-f]{16})\0", f.read())
+    return m.group(1).decode() if m else None
+
+
 def load():
-    """Load libwarmkv.so, building it first only if no built library exists."""
+    """Load libwarmkv.so.  The library carries a hash of the sources it was compiled from; if that
+    differs from the sources in the tree (or no library is there) it is built again first, and if
+    it still differs (or WARMKV_NO_REBUILD is set, for callers that must not compile) the call
+    raises StaleLibraryError: a stale binary is never used."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB_PATH):
+    want = _build.source_id()
+    have = _built_id(_build.LIB_PATH)
+    if have != want:
+        if os.environ.get("WARMKV_NO_REBUILD"):
+            raise StaleLibraryError(f"{_build.LIB_PATH}: built from sources {have}, the tree holds {want}")
+        print(f"warmkv: library is {have}, sources are {want}: building", file=sys.stderr, flush=True)
         _build.build()
+        have = _built_id(_build.LIB_PATH)
+        if have != want:
+            raise StaleLibraryError(f"{_build.LIB_PATH}: still {have} after a rebuild, the tree holds {want}")
     L = ctypes.CDLL(_build.LIB_PATH)
+    L.warmkv_build_id.restype = c_char_p
+    L.warmkv_build_id.argtypes = []
+    if L.warmkv_build_id().decode() != want:
+        raise StaleLibraryError(f"{_build.LIB_PATH}: loaded library says {L.warmkv_build_id().decode()}, wanted {want}")
     L.kv_plan_workspace_bytes.restype = c_size_t
     L.kv_plan_workspace_bytes.argtypes = [c_uint32, c_uint32]
     L.kv_plan_bind.restype = c_int
@@ -389,3 +420,7 @@ def ws_place_replicas(models, gpu_free_bytes, gpus_per_server: int):
 
 def warmkv_version() -> str:
     return load().warmkv_version().decode()
+
+
+def warmkv_build_id() -> str:
+    return load().warmkv_build_id().decode()

@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import glob
+import hashlib
 import os
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
@@ -24,15 +25,33 @@ def sources() -> list[str]:
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def inputs() -> list[str]:
+    """Every file whose text goes into the library: the sources and the headers they include."""
+    return sources() + sorted(glob.glob(os.path.join(CSRC, "*.h"))) + sorted(glob.glob(os.path.join(INCLUDE, "*.h")))
+
+
+def source_id() -> str:
+    """Hash of the current text of inputs() (names and bytes).  build() bakes it into the library,
+    which returns it from warmkv_build_id(); the binding compares the two before any call."""
+    h = hashlib.sha256()
+    for path in inputs():
+        h.update(os.path.basename(path).encode() + b"\0")
+        with open(path, "rb") as f:
+            h.update(f.read())
+        h.update(b"\0")
+    return h.hexdigest()[:16]
+
+
 def build(verbose: bool = False) -> str:
     """Compile every source and link the shared library; always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     srcs = sources()
+    build_id = source_id()
     objs = [os.path.join(OBJ_DIR, os.path.basename(s)[:-4] + ".o") for s in srcs]
 
     def compile_one(pair):
         src, obj = pair
-        cmd = ["hipcc", *HIPCC_FLAGS, "-c", src, "-o", obj]
+        cmd = ["hipcc", *HIPCC_FLAGS, f'-DWARMKV_BUILD_ID="{build_id}"', "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)

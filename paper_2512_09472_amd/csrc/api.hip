@@ -58,7 +58,9 @@ extern "C" int kv_plan_fetch(const kv_plan* plan, void* stream, kv_plan_state* o
   hipStream_t s = (hipStream_t)stream;
   int rc = hip_rc(hipMemcpyAsync(out, plan->state, sizeof(kv_plan_state), hipMemcpyDeviceToHost, s));
   if (rc != KV_OK) return rc;
-  return hip_rc(hipStreamSynchronize(s));
+  rc = hip_rc(hipStreamSynchronize(s));
+  if (rc == KV_OK && out->status == KV_OK && out->bad_plan != 0u) out->status = KV_E_BADPLAN;
+  return rc;
 }
 
 // Sec. 3.3, Eq. 4: R = max(C*Q/B, T + C/B).  The ceiling of a maximum is the
@@ -97,4 +99,12 @@ extern "C" int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint
   return lost;
 }
 
-extern "C" const char* warmkv_version(void) { return "0.1"; }
+extern "C" const char* warmkv_version(void) { return "0.2"; }
+
+// Hash of the sources this library was compiled from, passed in by the build.
+#ifndef WARMKV_BUILD_ID
+#define WARMKV_BUILD_ID "unknown"
+#endif
+// The tag in front lets a loader find the identifier in the file without loading it.
+static const char kBuildTag[] = "WARMKV_BUILD_ID=" WARMKV_BUILD_ID;
+extern "C" const char* warmkv_build_id(void) { return kBuildTag + 16; }

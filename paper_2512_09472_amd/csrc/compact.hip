@@ -26,7 +26,8 @@
 // evict anything.
 // Sources lie at or above the boundary and destinations below it, so no two
 // moves overlap and any order is correct; the kernel checks that property per
-// move instead of staging through LDS.
+// move instead of staging through LDS (a refused move is flagged in
+// state.bad_plan; state.status stays as the planner left it for the whole launch).
 #include "common.h"
 
 namespace warmkv {
@@ -131,7 +132,9 @@ __device__ __forceinline__ Unit resolve_unit(const CopyArgs& a, uint32_t ticket,
   }
   const uint32_t s = (uint32_t)a.src[k], d = (uint32_t)a.dst[k];
   if (s < a.boundary || s >= a.num_blocks || d >= a.boundary) {  // never true for a planner-made plan
-    atomicExch(&a.state->status, KV_E_BADPLAN);
+    // Flagged in a word of its own: `status` must not change while the launch runs, or workgroups
+    // that start later would see a different plan (no moves) and leave the counters dirty.
+    atomicExch(&a.state->bad_plan, 1u);
     return unit;
   }
   const uint64_t off = (uint64_t)g * a.seg_stride + (uint64_t)c * a.chunk_bytes;
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(kCopyThreads) void compact_packed_kernel(PackArgs a
           const uint32_t s = (uint32_t)a.src[k0 + i], d = (uint32_t)a.dst[k0 + i];
           const bool ok = s >= a.boundary && s < a.num_blocks && d < a.boundary;  // always true for a planner-made plan
           if (!ok) {
-            atomicExch(&a.state->status, KV_E_BADPLAN);
+            atomicExch(&a.state->bad_plan, 1u);  // not `status`: see resolve_unit
             refused = true;
           }
           s_src[i] = ok ? (uint64_t)s * a.block_stride + seg_off : kSkip;

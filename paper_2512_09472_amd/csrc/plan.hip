@@ -152,7 +152,8 @@ __global__ __launch_bounds__(THREADS) void plan_kernel(
     st.n_bad_entries = 0u;
     st.ticket = 0u;
     st.finished = 0u;
-    st.reserved[0] = st.reserved[1] = 0u;
+    st.bad_plan = 0u;
+    st.reserved = 0u;
     *state = st;
   }
   if (!feasible) return;  // uniform over the whole grid: nothing else is written

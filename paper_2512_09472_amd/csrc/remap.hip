@@ -25,7 +25,7 @@ __global__ __launch_bounds__(256) void remap_kernel(int32_t* tables, uint64_t n_
                                                     const int32_t* __restrict__ new_id,
                                                     uint32_t num_blocks,
                                                     kv_plan_state* __restrict__ state) {
-  if (state->status != KV_OK) return;
+  if (state->status != KV_OK || state->bad_plan != 0u) return;
   const uint64_t n_vec = n_entries / 4;
   const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
   const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;

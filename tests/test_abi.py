@@ -25,10 +25,47 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert set(names) == set(binding.EXPORTS), names
-    lib = ctypes.CDLL(binding.library_path()) if os.path.exists(binding.library_path()) else binding.load()
+    lib = binding.load()
     for n in names:
         assert hasattr(lib, n), n
-    assert wk.warmkv_version() == "0.1"
+    assert wk.warmkv_version() == "0.2"
+
+
+def test_loaded_library_was_built_from_the_sources_in_the_tree():
+    from paper_2512_09472_amd import build
+    binding.load()
+    assert binding.warmkv_build_id() == build.source_id() == binding._built_id(build.LIB_PATH)
+
+
+def test_a_changed_source_is_seen_and_a_stale_library_refused(tmp_path, monkeypatch):
+    """The identifier follows the text of every source and header; a library whose identifier
+    differs is rebuilt, or refused where rebuilding is switched off - never loaded as it is."""
+    import shutil
+    from paper_2512_09472_amd import build
+    before = build.source_id()
+    csrc, inc = tmp_path / "csrc", tmp_path / "include"
+    shutil.copytree(build.CSRC, csrc)
+    shutil.copytree(build.INCLUDE, inc)
+    monkeypatch.setattr(build, "CSRC", str(csrc))
+    monkeypatch.setattr(build, "INCLUDE", str(inc))
+    assert build.source_id() == before                       # same text, same identifier, wherever it lies
+    for touched in (csrc / "compact.hip", csrc / "common.h", inc / "warmkv.h"):
+        old = touched.read_bytes()
+        touched.write_bytes(old + b"\n// touched\n")
+        assert build.source_id() != before, touched
+        touched.write_bytes(old)
+    assert build.source_id() == before
+    (csrc / "remap.hip").write_bytes((csrc / "remap.hip").read_bytes() + b"\n")
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setenv("WARMKV_NO_REBUILD", "1")
+    with pytest.raises(binding.StaleLibraryError):
+        binding.load()
+    monkeypatch.delenv("WARMKV_NO_REBUILD")
+    calls = []
+    monkeypatch.setattr(build, "build", lambda verbose=False: calls.append(1))   # a build that changes nothing
+    with pytest.raises(binding.StaleLibraryError):
+        binding.load()
+    assert calls == [1]                                      # it did try to rebuild first
 
 
 def test_struct_sizes_match_the_header():

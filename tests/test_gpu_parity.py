@@ -283,6 +283,59 @@ def test_hand_built_bad_plan_is_refused_per_move(kv_heads):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("kv_heads,tuning", [(8, dict(workgroups=7, chunk_bytes=4096)),     # ticket kernel, 16 units per move
+                                             (1, dict(workgroups=3, chunk_bytes=16384))])   # packed kernel, two moves per ticket
+def test_bad_move_among_many_leaves_counters_clean(oracle, kv_heads, tuning):
+    """More units than workgroups, so tickets are drawn and every workgroup has to sign out.  One
+    move of a planner-made list is corrupted by hand: it is skipped and flagged, every other move
+    is copied, both counters are back at zero, and the same workspace then serves a fresh plan."""
+    cfg = CONFIGS[0].scaled(num_blocks=256, boundary=128, kv_heads=kv_heads, num_seqs=16)
+    w = make_workload(cfg)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    assert p.status == 0 and p.n_moves >= 12
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    live_d = gh.to_dev(w.live)
+    wk.kv_plan_reclaim(live_d, dp.plan)
+    torch.cuda.synchronize()
+    bad_k = 1                                   # an early move: most workgroups start after it was seen
+    src = p.src.copy()
+    src[bad_k] = int(p.dst[0])                  # a source below the boundary
+    dp._slice(dp.plan.src, 4 * p.n_moves).copy_(gh.to_dev(src))
+    wk.kv_compact_launch(pool, dp.plan, **tuning)
+    torch.cuda.synchronize()
+    st = dp.state()
+    assert st.status == wk.KV_E_BADPLAN and st.bad_plan == 1 and st.n_moves == p.n_moves
+    assert st.ticket == 0 and st.finished == 0
+    bb = cfg.block_bytes
+    want = pool0.copy()
+    good = oracle.Plan(0, np.delete(p.src, bad_k), np.delete(p.dst, bad_k), None, None, p.n_moves - 1,
+                       cfg.num_blocks, cfg.boundary)
+    oracle.compact(want, bb, good)
+    assert np.array_equal(pool_dev.cpu().numpy(), want), "valid moves must still be copied, the bad one skipped"
+    # the table rewrite refuses to follow a plan that was not carried out in full
+    tables_d = torch.from_numpy(w.tables).to(gh.dev())
+    wk.kv_remap_tables(tables_d, w.tables.shape[0], w.tables.shape[1], dp.plan)
+    torch.cuda.synchronize()
+    assert np.array_equal(tables_d.cpu().numpy(), w.tables)
+    # a fresh plan in the same workspace: exact against the oracle
+    pool_dev.copy_(torch.from_numpy(pool0))
+    wk.kv_plan_reclaim(live_d, dp.plan)
+    wk.kv_compact_launch(pool, dp.plan, **tuning)
+    wk.kv_remap_tables(tables_d, w.tables.shape[0], w.tables.shape[1], dp.plan)
+    torch.cuda.synchronize()
+    st = _compare_plan(dp, p)
+    assert st.bad_plan == 0 and st.ticket == 0 and st.finished == 0
+    want = pool0.copy()
+    oracle.compact(want, bb, p)
+    assert np.array_equal(pool_dev.cpu().numpy(), want)
+    want_t = w.tables.copy()
+    oracle.remap(want_t, p)
+    assert np.array_equal(tables_d.cpu().numpy(), want_t)
+
+
 def test_materialize_matches_oracle_and_overlaps_compaction(oracle):
     """Weights land byte-exactly in the reclaimed region, with the copy stream
     gated on the compaction event; bytes outside every extent keep their value."""

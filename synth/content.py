@@ -17,7 +17,9 @@ This is input generation only; it holds none of the reclaim method's logic.
 from __future__ import annotations
 
 import ctypes
+import hashlib
 import os
+import re
 import subprocess
 
 import numpy as np
@@ -70,10 +72,25 @@ def fill_host(dst: np.ndarray, item_bytes: int, cids, seed: int, table: np.ndarr
 # --------------------------------------------------------------------------
 # Device-side generator (same arithmetic, HIP).  Test/bench infrastructure.
 # --------------------------------------------------------------------------
+def _source_id() -> str:
+    with open(_SRC_PATH, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
+
+
+def _built_id() -> str | None:
+    if not os.path.exists(_LIB_PATH):
+        return None
+    with open(_LIB_PATH, "rb") as f:
+        m = re.search(rb"SYNTH_BUILD_ID=([0-9a-f]{16})\0", f.read())
+    return m.group(1).decode() if m else None
+
+
 def build_device_fill(force: bool = False) -> str:
-    if force or not os.path.exists(_LIB_PATH):
+    """Compile fill.hip unless the library at hand was built from this very source text."""
+    want = _source_id()
+    if force or _built_id() != want:
         cmd = ["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", f'-DSYNTH_BUILD_ID="{want}"',
                _SRC_PATH, "-o", _LIB_PATH]
         subprocess.run(cmd, check=True)
     return _LIB_PATH
@@ -91,8 +108,41 @@ def _load():
         lib.synth_fill.argtypes = [ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint64,
                                    ctypes.c_uint64, ctypes.c_void_p, ctypes.c_int64,
                                    ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+        lib.synth_host_alloc.restype = ctypes.c_void_p
+        lib.synth_host_alloc.argtypes = [ctypes.c_uint64]
+        lib.synth_host_free.restype = ctypes.c_int
+        lib.synth_host_free.argtypes = [ctypes.c_void_p]
+        lib.synth_copy.restype = ctypes.c_int
+        lib.synth_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64]
         _lib = lib
     return _lib
+
+
+class PinnedHostBuffer:
+    """Pinned host memory of exactly nbytes (torch's pinned allocator rounds sizes up to a power of
+    two, which a 40 GiB pool copy cannot afford).  ``array`` is a uint8 numpy view of it."""
+
+    def __init__(self, nbytes: int):
+        self.nbytes = nbytes
+        self.ptr = _load().synth_host_alloc(nbytes)
+        if not self.ptr:
+            raise MemoryError(f"cannot pin {nbytes} bytes of host memory")
+        self.array = np.ctypeslib.as_array((ctypes.c_uint8 * nbytes).from_address(self.ptr))
+
+    def free(self) -> None:
+        if self.ptr:
+            self.array = None
+            _load().synth_host_free(self.ptr)
+            self.ptr = None
+
+    def __del__(self):
+        self.free()
+
+
+def copy_bytes(dst_ptr: int, src_ptr: int, nbytes: int) -> None:
+    """Synchronous copy between any two of pinned host and device memory."""
+    if nbytes and _load().synth_copy(dst_ptr, src_ptr, nbytes) != 0:
+        raise RuntimeError("synth_copy failed")
 
 
 def fill_device(dst_ptr: int, n_items: int, item_bytes: int, seed: int, *,

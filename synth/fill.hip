@@ -62,3 +62,25 @@ extern "C" int synth_fill(void* dst, uint64_t n_items, uint64_t item_bytes, uint
                      (u64x2*)dst, n_items, units, seed, cids, cid0, table, word0);
   return hipGetLastError() == hipSuccess ? 0 : 2;
 }
+
+// Pinned host memory of an exact size for the harness (a host copy of a whole pool), and plain
+// synchronous copies to and from it.  Returns nullptr / non-zero on failure.
+extern "C" void* synth_host_alloc(uint64_t bytes) {
+  void* p = nullptr;
+  if (hipHostMalloc(&p, bytes, hipHostMallocDefault) == hipSuccess) return p;
+  (void)hipGetLastError();  // a refused allocation must not be reported by the caller's next call
+  return nullptr;
+}
+
+extern "C" int synth_host_free(void* p) { return hipHostFree(p) == hipSuccess ? 0 : 2; }
+
+extern "C" int synth_copy(void* dst, const void* src, uint64_t bytes) {
+  return hipMemcpy(dst, src, bytes, hipMemcpyDefault) == hipSuccess ? 0 : 2;
+}
+
+// Identifier of the source text this file was compiled from, passed in by the build.
+#ifndef SYNTH_BUILD_ID
+#define SYNTH_BUILD_ID "unknown"
+#endif
+static const char kSynthTag[] = "SYNTH_BUILD_ID=" SYNTH_BUILD_ID;
+extern "C" const char* synth_build_id(void) { return kSynthTag + 15; }

@@ -18,3 +18,11 @@ def oracle():
     import oracle as _oracle
     _oracle.build()
     return _oracle
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Lines that GPU tests want in the run's summary whatever the capture mode (which comparison
+    mode a full-size test used, for one)."""
+    harness = sys.modules.get("gpu_harness")
+    for line in getattr(harness, "SUMMARY", []):
+        terminalreporter.write_line(line)

@@ -10,6 +10,9 @@ import paper_2512_09472_amd as wk
 from synth import content
 
 
+SUMMARY: list[str] = []      # printed by conftest.pytest_terminal_summary at the end of the run
+
+
 def dev():
     return torch.device("cuda:0")
 

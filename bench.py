@@ -465,7 +465,7 @@ def main():
                 sys.exit(1)
 
     # ---- weight materialisation leg (third configuration: same pool plus weights)
-    weights_for_oracle = None
+    weights_for_oracle = host_weights = None
     if not args.no_materialize and cfg.index in (1, 2) and args.layout == "block" and not args.kv_heads:
         shapes = weight_shapes_8b()
         sizes = [2 * a * b for _, (a, b) in shapes]
@@ -598,6 +598,7 @@ def main():
                               "verified_how": "one more untimed run of each path on a freshly generated pool; tables, every "
                                               "block below the boundary, all 225 tensors and the region's tail compared "
                                               "byte for byte with the relocation rule written out in numpy"}
+        host_weights = (host, starts, sizes, offs)
         if args.no_cpu_baseline:
             weights_for_oracle = None
         del host
@@ -622,12 +623,30 @@ def main():
         t2 = time.perf_counter()
         wk.kv_vmm_restore(vp)
         t3 = time.perf_counter()
+        piped = None
+        if host_weights is not None and want * vcfg.block_bytes >= host_weights[3][-1] + host_weights[2][-1]:
+            # the paper's way of hiding the mapping cost: weight copies pipelined behind the mapping
+            h_t, h_starts, h_sizes, h_offs = host_weights
+            h_tensors = [(h_t.data_ptr() + a, b_, c) for a, b_, c in zip(h_starts, h_sizes, h_offs)]
+            vs = torch.cuda.Stream()
+            torch.cuda.synchronize()
+            t4 = time.perf_counter()
+            wk.kv_vmm_reclaim_load(vp, vw.live, want, h_tensors, vs.cuda_stream, 0)
+            t5 = time.perf_counter()
+            torch.cuda.synchronize()
+            t6 = time.perf_counter()
+            wk.kv_vmm_restore(vp)
+            piped = {"mapping_with_copies_enqueued_ms": round((t5 - t4) * 1e3, 1),
+                     "until_last_weight_byte_ms": round((t6 - t4) * 1e3, 1),
+                     "note": "kv_vmm_reclaim_load: 64 blocks mapped at a time, the weight bytes under each chunk enqueued "
+                             "on a copy stream as soon as it is mapped (225 tensors, 15,009,316,864 B)"}
         wk.kv_vmm_pool_destroy(vp)
         out["vmm_compare"] = {"workload": f"{vcfg.num_blocks} blocks of {vcfg.block_bytes} B, pages of the {want} highest "
                                           f"free blocks ({want * vcfg.block_bytes / 2**30:.2f} GiB) remapped into the slot",
                               "create_ms": round((t1 - t0) * 1e3, 1), "reclaim_ms": round((t2 - t1) * 1e3, 1),
                               "reclaim_us_per_block": round((t2 - t1) * 1e6 / want, 1),
-                              "restore_ms": round((t3 - t2) * 1e3, 1)}
+                              "restore_ms": round((t3 - t2) * 1e3, 1),
+                              "pipelined_with_weight_stream": piped}
 
     if not args.no_cpu_baseline:
         # bounded sample: every move of this workload, capped at 12 GiB moved (24 GiB of host memory touched)

@@ -57,6 +57,7 @@ extern "C" {
 #define KV_E_HIP      (-6)  /* a HIP call failed                                             */
 #define KV_E_NOSPACE  (-7)  /* device status: more movers than free ids below the boundary   */
 #define KV_E_BADPLAN  (-8)  /* device status: a move violates src >= boundary > dst          */
+#define KV_E_NOMEM    (-9)  /* host memory for the call's own bookkeeping could not be had   */
 
 /* Describes the caller-owned paged KV pool (one allocation).
  * layer_stride_bytes == 0: block-major.  Block i is block_bytes = L*tile_bytes
@@ -358,9 +359,28 @@ void* kv_vmm_slot_base(const kv_vmm_pool* pool);
  * ...; the slot prefix [0, want*block_bytes) is then readable and writable.
  * Those ids must not be touched through the KV range until kv_vmm_restore.
  * Fails with KV_E_NOSPACE (nothing changed) if fewer than `want` blocks are
- * free, KV_E_RANGE if pages are already lent.  ids_out [host, may be NULL]
- * receives the `want` ids.  Synchronises the device first. */
+ * free, KV_E_RANGE if pages are already lent.  If a driver call fails half way
+ * (KV_E_HIP) the pages lent so far are put back before the call returns; only
+ * if that fails too do pages stay in the slot, and kv_vmm_lent() says how many.
+ * ids_out [host, may be NULL] receives the `want` ids.  Synchronises the
+ * device first. */
 int kv_vmm_reclaim(kv_vmm_pool* pool, const uint64_t* live_host, uint32_t want, int32_t* ids_out);
+
+/* kv_vmm_reclaim with the weight stream pipelined behind the mapping, the way
+ * the paper hides its mapping cost (App. C: a copy is triggered as soon as its
+ * page is mapped).  Pages are handed over `chunk_blocks` blocks at a time
+ * (0 = 64); after each chunk the slot bytes it added are made accessible and
+ * every byte of `tensors` [host; dst_offset counts from the slot's start]
+ * that lies in them is enqueued on copy_stream from its pinned host_ptr, while
+ * this thread goes on mapping the next chunk.  Extents must lie inside
+ * [0, want*block_bytes) and be pairwise disjoint (KV_E_TOOBIG / KV_E_OVERLAP,
+ * checked before anything changes).  Returns after the last copy is enqueued;
+ * the host buffers must stay valid until copy_stream has drained. */
+int kv_vmm_reclaim_load(kv_vmm_pool* pool, const uint64_t* live_host, uint32_t want, uint32_t chunk_blocks,
+                        const wm_tensor* tensors, uint32_t n_tensors, void* copy_stream, int32_t* ids_out);
+
+/* Number of blocks whose pages are in the slot right now. */
+uint32_t kv_vmm_lent(const kv_vmm_pool* pool);
 
 /* Give every lent page back to its block's place in the KV range. */
 int kv_vmm_restore(kv_vmm_pool* pool);

@@ -68,6 +68,8 @@ def lib():
         L.oracle_grow.argtypes = [u64, u32, u32, u32, ctypes.POINTER(_Tensor), u32, vp, vp]
         L.oracle_reserve_blocks.restype = ctypes.c_int64
         L.oracle_reserve_blocks.argtypes = [u64, u64, u32, u32]
+        L.oracle_vmm_select.restype = ctypes.c_int
+        L.oracle_vmm_select.argtypes = [vp, u32, u32, vp]
         _lib = L
     return _lib
 
@@ -189,3 +191,17 @@ def grow(block_bytes: int, num_blocks: int, old_boundary: int, new_boundary: int
     if rc < 0:
         return rc, None, None
     return rc, ev[:len(extents)], no[:len(extents)]
+
+
+def vmm_select(live: np.ndarray, num_blocks: int, want: int):
+    """Blocks that lend their pages to the slot in the no-move variant, in slot order
+    (int32 array), or None if fewer than ``want`` blocks are free."""
+    live = np.ascontiguousarray(live, dtype=np.uint64)
+    assert live.size == (num_blocks + 63) // 64
+    ids = np.full(max(1, want), -1, dtype=np.int32)
+    rc = lib().oracle_vmm_select(_p(live if live.size else np.zeros(1, dtype=np.uint64)), num_blocks, want, _p(ids))
+    if rc == E_NOSPACE:
+        return None
+    if rc != OK:
+        raise ValueError(f"oracle_vmm_select: error {rc}")
+    return ids[:want]

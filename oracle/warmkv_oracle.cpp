@@ -232,4 +232,20 @@ int64_t oracle_grow(uint64_t block_bytes, uint32_t num_blocks, uint32_t old_boun
   return lost;
 }
 
+// No-move variant (Sec. 3.4; App. C, Fig. 4b steps 1-2): which unused blocks lend their physical
+// pages to the new model's slot.  Any `want` unused blocks would do for the paper; the reading
+// taken is "the `want` highest free ids, highest first", which keeps the low ids for the running
+// engine.  ids[k] is the block whose pages back slot offset k*block_bytes.
+// Returns ORACLE_E_NOSPACE (nothing written) if fewer than `want` blocks are free.
+int oracle_vmm_select(const uint64_t* live, uint32_t num_blocks, uint32_t want, int32_t* ids) {
+  if (!live || (want && !ids)) return ORACLE_E_NULL;
+  uint32_t n_free = 0;
+  for (uint32_t i = 0; i < num_blocks; ++i) n_free += !is_live(live, i);
+  if (want > n_free) return ORACLE_E_NOSPACE;
+  uint32_t k = 0;
+  for (uint32_t i = num_blocks; i > 0 && k < want; --i)
+    if (!is_live(live, i - 1)) ids[k++] = (int32_t)(i - 1);
+  return ORACLE_OK;
+}
+
 }  // extern "C"

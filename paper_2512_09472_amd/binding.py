@@ -26,17 +26,22 @@ KV_E_OVERLAP = -5
 KV_E_HIP = -6
 KV_E_NOSPACE = -7
 KV_E_BADPLAN = -8
+KV_E_NOMEM = -9
 
 _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E_ALIGN: "KV_E_ALIGN",
           KV_E_TOOBIG: "KV_E_TOOBIG", KV_E_OVERLAP: "KV_E_OVERLAP", KV_E_HIP: "KV_E_HIP",
-          KV_E_NOSPACE: "KV_E_NOSPACE", KV_E_BADPLAN: "KV_E_BADPLAN"}
+          KV_E_NOSPACE: "KV_E_NOSPACE", KV_E_BADPLAN: "KV_E_BADPLAN", KV_E_NOMEM: "KV_E_NOMEM"}
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
            "weights_materialize_pipelined", "kv_compact_moves", "kv_movers_in_front", "weights_materialize_front",
            "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
-           "kv_vmm_reclaim", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
+           "kv_vmm_reclaim", "kv_vmm_reclaim_load", "kv_vmm_lent", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
            "ws_place_replicas", "warmkv_version", "warmkv_build_id")
+
+
+__all__ = [*EXPORTS, "KV_OK", "KV_E_NULL", "KV_E_RANGE", "KV_E_ALIGN", "KV_E_TOOBIG", "KV_E_OVERLAP", "KV_E_HIP",
+           "KV_E_NOSPACE", "KV_E_BADPLAN", "KV_E_NOMEM", "WarmKVError", "StaleLibraryError", "pool_desc", "make_model"]
 
 
 class WarmKVError(RuntimeError):
@@ -180,6 +185,11 @@ def load():
     L.kv_vmm_slot_base.argtypes = [c_void_p]
     L.kv_vmm_reclaim.restype = c_int
     L.kv_vmm_reclaim.argtypes = [c_void_p, c_void_p, c_uint32, c_void_p]
+    L.kv_vmm_reclaim_load.restype = c_int
+    L.kv_vmm_reclaim_load.argtypes = [c_void_p, c_void_p, c_uint32, c_uint32, POINTER(wm_tensor), c_uint32, c_void_p,
+                                      c_void_p]
+    L.kv_vmm_lent.restype = c_uint32
+    L.kv_vmm_lent.argtypes = [c_void_p]
     L.kv_vmm_restore.restype = c_int
     L.kv_vmm_restore.argtypes = [c_void_p]
     L.kv_vmm_pool_destroy.restype = c_int
@@ -367,6 +377,21 @@ def kv_vmm_reclaim(pool: int, live_host, want: int) -> list[int]:
     live_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
     _check("kv_vmm_reclaim", load().kv_vmm_reclaim(pool, live_ptr, want, ids))
     return list(ids[:want])
+
+
+def kv_vmm_reclaim_load(pool: int, live_host, want: int, tensors, copy_stream=0, chunk_blocks: int = 0) -> list[int]:
+    """kv_vmm_reclaim with the weight stream pipelined behind the mapping.  tensors: iterable of
+    (pinned host buffer or address, bytes, offset from the slot's start)."""
+    ids = (c_int32 * max(1, want))()
+    arr, n = _tensor_array(tensors)
+    live_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
+    _check("kv_vmm_reclaim_load", load().kv_vmm_reclaim_load(pool, live_ptr, want, chunk_blocks, arr, n,
+                                                              _ptr(copy_stream), ids))
+    return list(ids[:want])
+
+
+def kv_vmm_lent(pool: int) -> int:
+    return int(load().kv_vmm_lent(pool))
 
 
 def kv_vmm_restore(pool: int) -> None:

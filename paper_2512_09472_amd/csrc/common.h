@@ -4,6 +4,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <new>
+
 #include "warmkv.h"
 
 namespace warmkv {
@@ -28,6 +30,19 @@ inline bool pool_extent_ok(const kv_pool_desc& p) {
   if (p.num_blocks != 0 && per_block > kMax / p.num_blocks) return false;
   if (p.layer_stride_bytes > kMax / p.num_layers) return false;
   return true;
+}
+
+// No exception may cross the C ABI: entry points that allocate host memory (std::vector) run
+// their body through this.
+template <class Body>
+inline auto guarded(Body&& body) noexcept -> decltype(body()) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return KV_E_NOMEM;
+  } catch (...) {
+    return KV_E_HIP;
+  }
 }
 
 // Launch status without clearing an earlier sticky error of the caller's.

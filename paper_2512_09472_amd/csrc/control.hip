@@ -87,61 +87,63 @@ extern "C" int ws_replica_scores(const ws_model* model, uint32_t* n_basic, uint3
 extern "C" int ws_place_replicas(const ws_model* models, uint32_t n_models, double* gpu_free_bytes,
                                  uint32_t n_gpus, uint32_t gpus_per_server, ws_placement* out, uint32_t capacity,
                                  uint32_t* n_out) {
-  if (n_out == nullptr || (n_models != 0 && models == nullptr) || (n_gpus != 0 && gpu_free_bytes == nullptr))
-    return KV_E_NULL;
-  if (gpus_per_server == 0 || n_gpus % gpus_per_server != 0) return KV_E_RANGE;
-  struct Replica {
-    uint32_t model, index, burst;
-    double score;
-  };
-  std::vector<Replica> replicas;
-  for (uint32_t i = 0; i < n_models; ++i) {
-    if (!model_ok(models[i]) || gpus_per_server % models[i].degree != 0) return KV_E_RANGE;
-    const Counts c = replica_counts(models[i]);
-    for (uint32_t r = 0; r < c.basic; ++r) replicas.push_back({i, r, 0u, replica_score(models[i], c, false, r)});
-    for (uint32_t r = 0; r < c.burst; ++r) replicas.push_back({i, c.basic + r, 1u, replica_score(models[i], c, true, r)});
-  }
-  std::stable_sort(replicas.begin(), replicas.end(), [](const Replica& a, const Replica& b) {
-    if (a.burst != b.burst) return a.burst < b.burst;  // basic replicas always come first
-    if (a.score != b.score) return a.score > b.score;
-    if (a.model != b.model) return a.model < b.model;
-    return a.index < b.index;
-  });
-
-  std::vector<double> free_bytes(gpu_free_bytes, gpu_free_bytes + n_gpus);  // committed only on success
-  std::vector<ws_placement> placed;
-  const double inf = std::numeric_limits<double>::infinity();
-  for (const Replica& r : replicas) {
-    const ws_model& m = models[r.model];
-    const double need = std::ceil(m.size_bytes / (double)m.degree);
-    int64_t best = -1, best_isolated = -1;
-    double best_sum = inf, best_isolated_sum = inf;
-    for (uint32_t g = 0; g + m.degree <= n_gpus; g += m.degree) {
-      bool fits = true;
-      for (uint32_t j = g; j < g + m.degree; ++j) fits = fits && free_bytes[j] >= need;
-      if (!fits) continue;
-      // H and R over the replicas that share a GPU with this group (aligned groups nest, so such
-      // a replica either covers the group or lies inside it)
-      double high = -inf, sum = 0.0;
-      for (const ws_placement& q : placed) {
-        const uint32_t q_end = q.first_gpu + models[q.model].degree;
-        if (q.first_gpu < g + m.degree && g < q_end) {
-          high = std::max(high, q.score);
-          sum += q.score;
-        }
-      }
-      if (best < 0 || sum < best_sum) { best_sum = sum; best = g; }
-      if (high < r.score && (best_isolated < 0 || sum < best_isolated_sum)) { best_isolated_sum = sum; best_isolated = g; }
+  return guarded([&]() -> int {
+    if (n_out == nullptr || (n_models != 0 && models == nullptr) || (n_gpus != 0 && gpu_free_bytes == nullptr))
+      return KV_E_NULL;
+    if (gpus_per_server == 0 || n_gpus % gpus_per_server != 0) return KV_E_RANGE;
+    struct Replica {
+      uint32_t model, index, burst;
+      double score;
+    };
+    std::vector<Replica> replicas;
+    for (uint32_t i = 0; i < n_models; ++i) {
+      if (!model_ok(models[i]) || gpus_per_server % models[i].degree != 0) return KV_E_RANGE;
+      const Counts c = replica_counts(models[i]);
+      for (uint32_t r = 0; r < c.basic; ++r) replicas.push_back({i, r, 0u, replica_score(models[i], c, false, r)});
+      for (uint32_t r = 0; r < c.burst; ++r) replicas.push_back({i, c.basic + r, 1u, replica_score(models[i], c, true, r)});
     }
-    if (best < 0) continue;  // no group has room: next replica
-    const uint32_t g = (uint32_t)(best_isolated >= 0 ? best_isolated : best);
-    for (uint32_t j = g; j < g + m.degree; ++j) free_bytes[j] -= need;
-    placed.push_back({r.model, r.index, g, r.burst, r.score});
-  }
-  *n_out = (uint32_t)placed.size();
-  if (placed.size() > capacity) return KV_E_TOOBIG;
-  if (!placed.empty() && out == nullptr) return KV_E_NULL;
-  std::copy(placed.begin(), placed.end(), out);
-  std::copy(free_bytes.begin(), free_bytes.end(), gpu_free_bytes);
-  return KV_OK;
+    std::stable_sort(replicas.begin(), replicas.end(), [](const Replica& a, const Replica& b) {
+      if (a.burst != b.burst) return a.burst < b.burst;  // basic replicas always come first
+      if (a.score != b.score) return a.score > b.score;
+      if (a.model != b.model) return a.model < b.model;
+      return a.index < b.index;
+    });
+  
+    std::vector<double> free_bytes(gpu_free_bytes, gpu_free_bytes + n_gpus);  // committed only on success
+    std::vector<ws_placement> placed;
+    const double inf = std::numeric_limits<double>::infinity();
+    for (const Replica& r : replicas) {
+      const ws_model& m = models[r.model];
+      const double need = std::ceil(m.size_bytes / (double)m.degree);
+      int64_t best = -1, best_isolated = -1;
+      double best_sum = inf, best_isolated_sum = inf;
+      for (uint32_t g = 0; g + m.degree <= n_gpus; g += m.degree) {
+        bool fits = true;
+        for (uint32_t j = g; j < g + m.degree; ++j) fits = fits && free_bytes[j] >= need;
+        if (!fits) continue;
+        // H and R over the replicas that share a GPU with this group (aligned groups nest, so such
+        // a replica either covers the group or lies inside it)
+        double high = -inf, sum = 0.0;
+        for (const ws_placement& q : placed) {
+          const uint32_t q_end = q.first_gpu + models[q.model].degree;
+          if (q.first_gpu < g + m.degree && g < q_end) {
+            high = std::max(high, q.score);
+            sum += q.score;
+          }
+        }
+        if (best < 0 || sum < best_sum) { best_sum = sum; best = g; }
+        if (high < r.score && (best_isolated < 0 || sum < best_isolated_sum)) { best_isolated_sum = sum; best_isolated = g; }
+      }
+      if (best < 0) continue;  // no group has room: next replica
+      const uint32_t g = (uint32_t)(best_isolated >= 0 ? best_isolated : best);
+      for (uint32_t j = g; j < g + m.degree; ++j) free_bytes[j] -= need;
+      placed.push_back({r.model, r.index, g, r.burst, r.score});
+    }
+    *n_out = (uint32_t)placed.size();
+    if (placed.size() > capacity) return KV_E_TOOBIG;
+    if (!placed.empty() && out == nullptr) return KV_E_NULL;
+    std::copy(placed.begin(), placed.end(), out);
+    std::copy(free_bytes.begin(), free_bytes.end(), gpu_free_bytes);
+    return KV_OK;
+  });
 }

@@ -168,74 +168,80 @@ using namespace warmkv;
 
 extern "C" int weights_materialize(const kv_pool_desc* pool, uint32_t boundary, const wm_tensor* tensors,
                                    uint32_t n_tensors, void* copy_stream, void* compaction_done) {
-  Region r;
-  int rc = validate(pool, boundary, tensors, n_tensors, &r);
-  if (rc != KV_OK) return rc;
-  hipStream_t s = (hipStream_t)copy_stream;
-  if (compaction_done != nullptr) {
-    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+  return guarded([&]() -> int {
+    Region r;
+    int rc = validate(pool, boundary, tensors, n_tensors, &r);
     if (rc != KV_OK) return rc;
-  }
-  Requests requests(s);
-  for (uint32_t i = 0; i < n_tensors; ++i) {  // caller's order
-    if (tensors[i].bytes == 0) continue;
-    rc = requests.add(region_address(pool, r, tensors[i].dst_offset), (const uint8_t*)tensors[i].host_ptr,
-                      tensors[i].bytes);
-    if (rc != KV_OK) return rc;
-  }
-  return requests.flush();
+    hipStream_t s = (hipStream_t)copy_stream;
+    if (compaction_done != nullptr) {
+      rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+      if (rc != KV_OK) return rc;
+    }
+    Requests requests(s);
+    for (uint32_t i = 0; i < n_tensors; ++i) {  // caller's order
+      if (tensors[i].bytes == 0) continue;
+      rc = requests.add(region_address(pool, r, tensors[i].dst_offset), (const uint8_t*)tensors[i].host_ptr,
+                        tensors[i].bytes);
+      if (rc != KV_OK) return rc;
+    }
+    return requests.flush();
+  });
 }
 
 extern "C" int weights_materialize_schedule(const kv_pool_desc* pool, uint32_t boundary,
                                             const uint64_t* live_host, const wm_tensor* tensors,
                                             uint32_t n_tensors, uint64_t early_bytes, wm_piece* out,
                                             uint32_t capacity, uint32_t* n_out) {
-  Region r;
-  const int rc = validate(pool, boundary, tensors, n_tensors, &r);
-  if (rc != KV_OK) return rc;
-  if (n_out == nullptr || (capacity != 0 && out == nullptr)) return KV_E_NULL;
-  if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
-  if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
-  std::vector<wm_piece> early, late;
-  schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
-  const size_t total = early.size() + late.size();
-  if (total > 0xFFFFFFFFull) return KV_E_RANGE;
-  *n_out = (uint32_t)total;
-  if (total > capacity) return KV_E_TOOBIG;
-  std::copy(early.begin(), early.end(), out);
-  std::copy(late.begin(), late.end(), out + early.size());
-  return KV_OK;
+  return guarded([&]() -> int {
+    Region r;
+    const int rc = validate(pool, boundary, tensors, n_tensors, &r);
+    if (rc != KV_OK) return rc;
+    if (n_out == nullptr || (capacity != 0 && out == nullptr)) return KV_E_NULL;
+    if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
+    if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
+    std::vector<wm_piece> early, late;
+    schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
+    const size_t total = early.size() + late.size();
+    if (total > 0xFFFFFFFFull) return KV_E_RANGE;
+    *n_out = (uint32_t)total;
+    if (total > capacity) return KV_E_TOOBIG;
+    std::copy(early.begin(), early.end(), out);
+    std::copy(late.begin(), late.end(), out + early.size());
+    return KV_OK;
+  });
 }
 
 extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
                                              const uint64_t* live_host, const wm_tensor* tensors,
                                              uint32_t n_tensors, uint64_t early_bytes, void* copy_stream,
                                              void* compaction_done) {
-  Region r;
-  int rc = validate(pool, boundary, tensors, n_tensors, &r);
-  if (rc != KV_OK) return rc;
-  if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
-  if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
-  std::vector<wm_piece> early, late;
-  schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
-  hipStream_t s = (hipStream_t)copy_stream;
-  uint8_t* region = (uint8_t*)pool->base + r.offset;
-  Requests requests(s);
-  for (const wm_piece& p : early) {
-    rc = requests.add(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes);
+  return guarded([&]() -> int {
+    Region r;
+    int rc = validate(pool, boundary, tensors, n_tensors, &r);
     if (rc != KV_OK) return rc;
-  }
-  rc = requests.flush();
-  if (rc != KV_OK) return rc;
-  if (compaction_done != nullptr) {
-    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+    if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
+    if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
+    std::vector<wm_piece> early, late;
+    schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
+    hipStream_t s = (hipStream_t)copy_stream;
+    uint8_t* region = (uint8_t*)pool->base + r.offset;
+    Requests requests(s);
+    for (const wm_piece& p : early) {
+      rc = requests.add(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes);
+      if (rc != KV_OK) return rc;
+    }
+    rc = requests.flush();
     if (rc != KV_OK) return rc;
-  }
-  for (const wm_piece& p : late) {
-    rc = requests.add(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes);
-    if (rc != KV_OK) return rc;
-  }
-  return requests.flush();
+    if (compaction_done != nullptr) {
+      rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+      if (rc != KV_OK) return rc;
+    }
+    for (const wm_piece& p : late) {
+      rc = requests.add(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes);
+      if (rc != KV_OK) return rc;
+    }
+    return requests.flush();
+  });
 }
 
 extern "C" uint32_t kv_movers_in_front(const uint64_t* live_host, uint32_t num_blocks, uint32_t boundary,
@@ -255,37 +261,39 @@ extern "C" uint32_t kv_movers_in_front(const uint64_t* live_host, uint32_t num_b
 extern "C" int weights_materialize_front(const kv_pool_desc* pool, uint32_t boundary, uint64_t front_bytes,
                                          const wm_tensor* tensors, uint32_t n_tensors, void* copy_stream,
                                          void* front_done, void* compaction_done) {
-  Region r;
-  int rc = validate(pool, boundary, tensors, n_tensors, &r);
-  if (rc != KV_OK) return rc;
-  if (r.layer_major) return KV_E_RANGE;
-  hipStream_t s = (hipStream_t)copy_stream;
-  uint8_t* region = (uint8_t*)pool->base + r.offset;
-  auto front_part = [&](const wm_tensor& t) -> uint64_t {  // leading bytes of t that lie below the mark
-    return t.dst_offset >= front_bytes ? 0 : std::min(t.bytes, front_bytes - t.dst_offset);
-  };
-  if (front_done != nullptr) {
-    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)front_done, 0));
+  return guarded([&]() -> int {
+    Region r;
+    int rc = validate(pool, boundary, tensors, n_tensors, &r);
     if (rc != KV_OK) return rc;
-  }
-  Requests requests(s);
-  for (uint32_t i = 0; i < n_tensors; ++i) {
-    rc = requests.add(region + tensors[i].dst_offset, (const uint8_t*)tensors[i].host_ptr, front_part(tensors[i]));
+    if (r.layer_major) return KV_E_RANGE;
+    hipStream_t s = (hipStream_t)copy_stream;
+    uint8_t* region = (uint8_t*)pool->base + r.offset;
+    auto front_part = [&](const wm_tensor& t) -> uint64_t {  // leading bytes of t that lie below the mark
+      return t.dst_offset >= front_bytes ? 0 : std::min(t.bytes, front_bytes - t.dst_offset);
+    };
+    if (front_done != nullptr) {
+      rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)front_done, 0));
+      if (rc != KV_OK) return rc;
+    }
+    Requests requests(s);
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+      rc = requests.add(region + tensors[i].dst_offset, (const uint8_t*)tensors[i].host_ptr, front_part(tensors[i]));
+      if (rc != KV_OK) return rc;
+    }
+    rc = requests.flush();
     if (rc != KV_OK) return rc;
-  }
-  rc = requests.flush();
-  if (rc != KV_OK) return rc;
-  if (compaction_done != nullptr) {
-    rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
-    if (rc != KV_OK) return rc;
-  }
-  for (uint32_t i = 0; i < n_tensors; ++i) {
-    const uint64_t head = front_part(tensors[i]);
-    rc = requests.add(region + tensors[i].dst_offset + head, (const uint8_t*)tensors[i].host_ptr + head,
-                      tensors[i].bytes - head);
-    if (rc != KV_OK) return rc;
-  }
-  return requests.flush();
+    if (compaction_done != nullptr) {
+      rc = hip_rc(hipStreamWaitEvent(s, (hipEvent_t)compaction_done, 0));
+      if (rc != KV_OK) return rc;
+    }
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+      const uint64_t head = front_part(tensors[i]);
+      rc = requests.add(region + tensors[i].dst_offset + head, (const uint8_t*)tensors[i].host_ptr + head,
+                        tensors[i].bytes - head);
+      if (rc != KV_OK) return rc;
+    }
+    return requests.flush();
+  });
 }
 
 // The whole hand-over in one call.  The separate entry points leave one gap
@@ -295,58 +303,60 @@ extern "C" int weights_materialize_front(const kv_pool_desc* pool, uint32_t boun
 // host synchronisation, microseconds against a weight stream of hundreds of
 // milliseconds) before anything that writes the pool is enqueued.
 extern "C" int kv_switch(const kv_switch_request* rq, kv_plan_state* result) {
-  if (rq == nullptr || rq->pool == nullptr || rq->plan == nullptr || rq->compaction_done == nullptr) return KV_E_NULL;
-  const kv_pool_desc* pool = rq->pool;
-  const kv_plan* plan = rq->plan;
-  if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
-  if (!pool_extent_ok(*pool)) return KV_E_RANGE;
-  if ((pool->tile_bytes % 16u) != 0 || ((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
-  const uint64_t n_entries = (uint64_t)rq->num_seqs * rq->max_blocks_per_seq;
-  if (n_entries != 0 && rq->tables == nullptr) return KV_E_NULL;
-  if (((uintptr_t)rq->tables % 16u) != 0) return KV_E_ALIGN;
-  Region r;
-  int rc = validate(pool, plan->boundary, rq->tensors, rq->n_tensors, &r);
-  if (rc != KV_OK) return rc;
-
-  rc = kv_plan_reclaim(rq->live_in, plan, rq->compute_stream);
-  if (rc != KV_OK) return rc;
-  kv_plan_state st;
-  rc = kv_plan_fetch(plan, rq->compute_stream, &st);
-  if (rc != KV_OK) return rc;
-  if (result != nullptr) *result = st;
-  if (st.status != KV_OK) return st.status;  // running requests keep their blocks; no weight byte is sent
-
-  const bool can_pipeline = rq->live_host != nullptr && !r.layer_major && r.block_bytes != 0;
-  const bool front_first = can_pipeline && rq->front_done != nullptr && rq->n_tensors != 0;
-  uint64_t front_bytes = 0;
-  if (front_first) {
-    // Enough weight bytes below the mark to keep the link busy until the block copy has ended:
-    // the link carries roughly 1/120 of what the block copy moves in the same time; twice that.
-    const uint64_t moved = 2ull * st.n_moves * r.block_bytes;
-    front_bytes = rq->early_bytes ? rq->early_bytes : std::max<uint64_t>(64ull << 20, moved / 64);
-    const uint64_t front_blocks =
-        std::min<uint64_t>((front_bytes + r.block_bytes - 1) / r.block_bytes, pool->num_blocks - plan->boundary);
-    front_bytes = front_blocks * r.block_bytes;
-    const uint32_t head = kv_movers_in_front(rq->live_host, pool->num_blocks, plan->boundary, (uint32_t)front_blocks);
-    rc = kv_compact_moves(pool, plan, 0u, head, rq->compute_stream);
+  return guarded([&]() -> int {
+    if (rq == nullptr || rq->pool == nullptr || rq->plan == nullptr || rq->compaction_done == nullptr) return KV_E_NULL;
+    const kv_pool_desc* pool = rq->pool;
+    const kv_plan* plan = rq->plan;
+    if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
+    if (!pool_extent_ok(*pool)) return KV_E_RANGE;
+    if ((pool->tile_bytes % 16u) != 0 || ((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
+    const uint64_t n_entries = (uint64_t)rq->num_seqs * rq->max_blocks_per_seq;
+    if (n_entries != 0 && rq->tables == nullptr) return KV_E_NULL;
+    if (((uintptr_t)rq->tables % 16u) != 0) return KV_E_ALIGN;
+    Region r;
+    int rc = validate(pool, plan->boundary, rq->tensors, rq->n_tensors, &r);
     if (rc != KV_OK) return rc;
-    rc = hip_rc(hipEventRecord((hipEvent_t)rq->front_done, (hipStream_t)rq->compute_stream));
+  
+    rc = kv_plan_reclaim(rq->live_in, plan, rq->compute_stream);
     if (rc != KV_OK) return rc;
-    rc = kv_compact_moves(pool, plan, head, ~0u, rq->compute_stream);
-  } else {
-    rc = kv_compact(pool, plan, rq->compute_stream);
-  }
-  if (rc != KV_OK) return rc;
-  rc = hip_rc(hipEventRecord((hipEvent_t)rq->compaction_done, (hipStream_t)rq->compute_stream));
-  if (rc != KV_OK) return rc;
-  rc = kv_remap_tables(rq->tables, rq->num_seqs, rq->max_blocks_per_seq, plan, rq->compute_stream);
-  if (rc != KV_OK) return rc;
-  if (front_first)
-    return weights_materialize_front(pool, plan->boundary, front_bytes, rq->tensors, rq->n_tensors, rq->copy_stream,
-                                     rq->front_done, rq->compaction_done);
-  if (can_pipeline)
-    return weights_materialize_pipelined(pool, plan->boundary, rq->live_host, rq->tensors, rq->n_tensors,
-                                         rq->early_bytes, rq->copy_stream, rq->compaction_done);
-  return weights_materialize(pool, plan->boundary, rq->tensors, rq->n_tensors, rq->copy_stream,
-                             rq->compaction_done);
+    kv_plan_state st;
+    rc = kv_plan_fetch(plan, rq->compute_stream, &st);
+    if (rc != KV_OK) return rc;
+    if (result != nullptr) *result = st;
+    if (st.status != KV_OK) return st.status;  // running requests keep their blocks; no weight byte is sent
+  
+    const bool can_pipeline = rq->live_host != nullptr && !r.layer_major && r.block_bytes != 0;
+    const bool front_first = can_pipeline && rq->front_done != nullptr && rq->n_tensors != 0;
+    uint64_t front_bytes = 0;
+    if (front_first) {
+      // Enough weight bytes below the mark to keep the link busy until the block copy has ended:
+      // the link carries roughly 1/120 of what the block copy moves in the same time; twice that.
+      const uint64_t moved = 2ull * st.n_moves * r.block_bytes;
+      front_bytes = rq->early_bytes ? rq->early_bytes : std::max<uint64_t>(64ull << 20, moved / 64);
+      const uint64_t front_blocks =
+          std::min<uint64_t>((front_bytes + r.block_bytes - 1) / r.block_bytes, pool->num_blocks - plan->boundary);
+      front_bytes = front_blocks * r.block_bytes;
+      const uint32_t head = kv_movers_in_front(rq->live_host, pool->num_blocks, plan->boundary, (uint32_t)front_blocks);
+      rc = kv_compact_moves(pool, plan, 0u, head, rq->compute_stream);
+      if (rc != KV_OK) return rc;
+      rc = hip_rc(hipEventRecord((hipEvent_t)rq->front_done, (hipStream_t)rq->compute_stream));
+      if (rc != KV_OK) return rc;
+      rc = kv_compact_moves(pool, plan, head, ~0u, rq->compute_stream);
+    } else {
+      rc = kv_compact(pool, plan, rq->compute_stream);
+    }
+    if (rc != KV_OK) return rc;
+    rc = hip_rc(hipEventRecord((hipEvent_t)rq->compaction_done, (hipStream_t)rq->compute_stream));
+    if (rc != KV_OK) return rc;
+    rc = kv_remap_tables(rq->tables, rq->num_seqs, rq->max_blocks_per_seq, plan, rq->compute_stream);
+    if (rc != KV_OK) return rc;
+    if (front_first)
+      return weights_materialize_front(pool, plan->boundary, front_bytes, rq->tensors, rq->n_tensors, rq->copy_stream,
+                                       rq->front_done, rq->compaction_done);
+    if (can_pipeline)
+      return weights_materialize_pipelined(pool, plan->boundary, rq->live_host, rq->tensors, rq->n_tensors,
+                                           rq->early_bytes, rq->copy_stream, rq->compaction_done);
+    return weights_materialize(pool, plan->boundary, rq->tensors, rq->n_tensors, rq->copy_stream,
+                               rq->compaction_done);
+  });
 }

@@ -5,6 +5,7 @@
 // unmapped there and mapped back to back into a second range (the "prewarm
 // slot").  No byte is copied and no block table changes; the cost is one
 // unmap and one map call per block plus one access grant.
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -41,10 +42,72 @@ int grant(void* ptr, size_t bytes, int device) {
   return hip_rc(hipMemSetAccess(ptr, bytes, &desc, 1));
 }
 
+// Put the pages of the last lent blocks back under their ids until `keep` are left in the slot.
+// Access is granted once, over the span of ids that came back (everything in it is mapped again
+// or was never unmapped), instead of block by block.
+int give_back(kv_vmm_pool* pool, size_t keep) {
+  const uint64_t bb = pool->block_bytes;
+  uint32_t lo = ~0u, hi = 0u;
+  while (pool->lent.size() > keep) {
+    const size_t k = pool->lent.size() - 1;
+    const uint32_t id = (uint32_t)pool->lent[k];
+    if (hipMemUnmap(pool->slot_base + (uint64_t)k * bb, bb) != hipSuccess) return KV_E_HIP;
+    pool->lent.pop_back();
+    if (hipMemMap(pool->kv_base + (uint64_t)id * bb, bb, 0, pool->handles[id], 0) != hipSuccess) return KV_E_HIP;
+    pool->in_kv[id] = 1;
+    lo = std::min(lo, id);
+    hi = std::max(hi, id);
+  }
+  if (lo > hi) return KV_OK;  // nothing came back
+  // A span may hold ids that are still lent (keep != 0): grant run by run of mapped ids.
+  for (uint32_t i = lo; i <= hi;) {
+    if (!pool->in_kv[i]) { ++i; continue; }
+    uint32_t j = i;
+    while (j <= hi && pool->in_kv[j]) ++j;
+    const int rc = grant(pool->kv_base + (uint64_t)i * bb, (size_t)(j - i) * bb, pool->device);
+    if (rc != KV_OK) return rc;
+    i = j;
+  }
+  return KV_OK;
+}
+
+// The `want` highest unused ids, highest first (empty if there are fewer).
+std::vector<int32_t> highest_free(const kv_vmm_pool* pool, const uint64_t* live_host, uint32_t want) {
+  std::vector<int32_t> ids;
+  ids.reserve(want);
+  for (uint32_t i = pool->num_blocks; i-- > 0 && ids.size() < want;)
+    if (!((live_host[i >> 6] >> (i & 63)) & 1ull)) ids.push_back((int32_t)i);
+  if (ids.size() < want) ids.clear();
+  return ids;
+}
+
+// Move the pages of ids[first, end) into the slot at their slot positions and make them
+// accessible.  On failure the caller rolls back with give_back().
+int lend(kv_vmm_pool* pool, const std::vector<int32_t>& ids, uint32_t first, uint32_t end) {
+  const uint64_t bb = pool->block_bytes;
+  for (uint32_t k = first; k < end; ++k) {
+    const uint32_t id = (uint32_t)ids[k];
+    if (hipMemUnmap(pool->kv_base + (uint64_t)id * bb, bb) != hipSuccess) return KV_E_HIP;
+    pool->in_kv[id] = 0;
+    if (hipMemMap(pool->slot_base + (uint64_t)k * bb, bb, 0, pool->handles[id], 0) != hipSuccess) {
+      // put the page back where it was so that the pool stays consistent
+      if (hipMemMap(pool->kv_base + (uint64_t)id * bb, bb, 0, pool->handles[id], 0) == hipSuccess &&
+          grant(pool->kv_base + (uint64_t)id * bb, bb, pool->device) == KV_OK)
+        pool->in_kv[id] = 1;
+      return KV_E_HIP;
+    }
+    pool->lent.push_back((int32_t)id);
+  }
+  if (end == first) return KV_OK;
+  return grant(pool->slot_base + (uint64_t)first * bb, (size_t)(end - first) * bb, pool->device);
+}
+
 }  // namespace
 }  // namespace warmkv
 
 using namespace warmkv;
+
+static int create_pool(uint32_t num_blocks, uint64_t block_bytes, kv_vmm_pool** out);
 
 extern "C" int kv_vmm_pool_destroy(kv_vmm_pool* pool) {
   if (pool == nullptr) return KV_E_NULL;
@@ -64,6 +127,10 @@ extern "C" int kv_vmm_pool_destroy(kv_vmm_pool* pool) {
 }
 
 extern "C" int kv_vmm_pool_create(uint32_t num_blocks, uint64_t block_bytes, kv_vmm_pool** out) {
+  return guarded([&]() -> int { return create_pool(num_blocks, block_bytes, out); });
+}
+
+static int create_pool(uint32_t num_blocks, uint64_t block_bytes, kv_vmm_pool** out) {
   if (out == nullptr) return KV_E_NULL;
   *out = nullptr;
   if (num_blocks == 0 || num_blocks > kMaxBlocks || block_bytes == 0) return KV_E_RANGE;
@@ -80,9 +147,15 @@ extern "C" int kv_vmm_pool_create(uint32_t num_blocks, uint64_t block_bytes, kv_
   p->device = device;
   p->num_blocks = num_blocks;
   p->block_bytes = block_bytes;
-  p->handles.resize(num_blocks);
-  p->have_handle.assign(num_blocks, 0);
-  p->in_kv.assign(num_blocks, 0);
+  try {
+    p->handles.resize(num_blocks);
+    p->have_handle.assign(num_blocks, 0);
+    p->in_kv.assign(num_blocks, 0);
+    p->lent.reserve(num_blocks);  // so that lending never allocates
+  } catch (...) {
+    delete p;
+    throw;
+  }
   const size_t range = (size_t)num_blocks * block_bytes;
   void* a = nullptr;
   void* b = nullptr;
@@ -108,50 +181,71 @@ extern "C" void* kv_vmm_kv_base(const kv_vmm_pool* pool) { return pool ? pool->k
 extern "C" void* kv_vmm_slot_base(const kv_vmm_pool* pool) { return pool ? pool->slot_base : nullptr; }
 
 extern "C" int kv_vmm_reclaim(kv_vmm_pool* pool, const uint64_t* live_host, uint32_t want, int32_t* ids_out) {
-  if (pool == nullptr || live_host == nullptr) return KV_E_NULL;
-  if (!pool->lent.empty()) return KV_E_RANGE;
-  if (want == 0) return KV_OK;
-  std::vector<int32_t> ids;
-  ids.reserve(want);
-  for (uint32_t i = pool->num_blocks; i-- > 0 && ids.size() < want;)
-    if (!((live_host[i >> 6] >> (i & 63)) & 1ull)) ids.push_back((int32_t)i);
-  if (ids.size() < want) return KV_E_NOSPACE;
-  int rc = hip_rc(hipDeviceSynchronize());  // nothing may be in flight on pages that change address
-  if (rc != KV_OK) return rc;
-  const uint64_t bb = pool->block_bytes;
-  for (uint32_t k = 0; k < want; ++k) {
-    const uint32_t id = (uint32_t)ids[k];
-    if (hipMemUnmap(pool->kv_base + (uint64_t)id * bb, bb) != hipSuccess) return KV_E_HIP;
-    pool->in_kv[id] = 0;
-    if (hipMemMap(pool->slot_base + (uint64_t)k * bb, bb, 0, pool->handles[id], 0) != hipSuccess) {
-      // put the page back where it was so that the pool stays consistent
-      if (hipMemMap(pool->kv_base + (uint64_t)id * bb, bb, 0, pool->handles[id], 0) == hipSuccess &&
-          grant(pool->kv_base + (uint64_t)id * bb, bb, pool->device) == KV_OK)
-        pool->in_kv[id] = 1;
-      return KV_E_HIP;
-    }
-    pool->lent.push_back((int32_t)id);
-  }
-  rc = grant(pool->slot_base, (size_t)want * bb, pool->device);
-  if (rc != KV_OK) return rc;
-  if (ids_out != nullptr) std::copy(ids.begin(), ids.end(), ids_out);
-  return KV_OK;
+  return kv_vmm_reclaim_load(pool, live_host, want, want, nullptr, 0, nullptr, ids_out);
 }
+
+extern "C" int kv_vmm_reclaim_load(kv_vmm_pool* pool, const uint64_t* live_host, uint32_t want, uint32_t chunk_blocks,
+                                   const wm_tensor* tensors, uint32_t n_tensors, void* copy_stream, int32_t* ids_out) {
+  return guarded([&]() -> int {
+    if (pool == nullptr || live_host == nullptr || (n_tensors != 0 && tensors == nullptr)) return KV_E_NULL;
+    if (!pool->lent.empty()) return KV_E_RANGE;
+    const uint64_t bb = pool->block_bytes;
+    const uint64_t slot_bytes = (uint64_t)want * bb;
+    // weight extents: inside the slot prefix, pairwise disjoint, before anything changes
+    std::vector<uint32_t> order;
+    for (uint32_t i = 0; i < n_tensors; ++i) {
+      if (tensors[i].dst_offset > slot_bytes || tensors[i].bytes > slot_bytes - tensors[i].dst_offset) return KV_E_TOOBIG;
+      if (tensors[i].bytes == 0) continue;
+      if (tensors[i].host_ptr == nullptr) return KV_E_NULL;
+      order.push_back(i);
+    }
+    std::sort(order.begin(), order.end(),
+              [&](uint32_t a, uint32_t b) { return tensors[a].dst_offset < tensors[b].dst_offset; });
+    for (size_t j = 1; j < order.size(); ++j)
+      if (tensors[order[j - 1]].dst_offset + tensors[order[j - 1]].bytes > tensors[order[j]].dst_offset)
+        return KV_E_OVERLAP;
+    if (want == 0) return KV_OK;
+    const std::vector<int32_t> ids = highest_free(pool, live_host, want);
+    if (ids.empty()) return KV_E_NOSPACE;
+    int rc = hip_rc(hipDeviceSynchronize());  // nothing may be in flight on pages that change address
+    if (rc != KV_OK) return rc;
+    if (chunk_blocks == 0) chunk_blocks = 64;
+    size_t next = 0;  // first extent (in offset order) that still has bytes to send
+    uint64_t sent_to = 0;  // slot offset up to which extent order[next] has been sent
+    for (uint32_t first = 0; first < want; first += chunk_blocks) {
+      const uint32_t end = want - first < chunk_blocks ? want : first + chunk_blocks;
+      rc = lend(pool, ids, first, end);
+      if (rc != KV_OK) {
+        // Copies already enqueued target pages that are about to leave the slot: let them land first.
+        if (n_tensors != 0) (void)hipStreamSynchronize((hipStream_t)copy_stream);
+        (void)give_back(pool, 0);
+        return rc;
+      }
+      // every weight byte below the mapped mark goes out now, in offset order
+      const uint64_t mark = (uint64_t)end * bb;
+      while (next < order.size()) {
+        const wm_tensor& t = tensors[order[next]];
+        const uint64_t from = std::max(sent_to, t.dst_offset), to = std::min(mark, t.dst_offset + t.bytes);
+        if (from < to) {
+          rc = hip_rc(hipMemcpyAsync(pool->slot_base + from, (const uint8_t*)t.host_ptr + (from - t.dst_offset),
+                                     to - from, hipMemcpyHostToDevice, (hipStream_t)copy_stream));
+          if (rc != KV_OK) return rc;  // the pages stay lent; kv_vmm_restore puts them back
+        }
+        if (t.dst_offset + t.bytes > mark) { sent_to = mark; break; }
+        sent_to = 0;
+        ++next;
+      }
+    }
+    if (ids_out != nullptr) std::copy(ids.begin(), ids.end(), ids_out);
+    return KV_OK;
+  });
+}
+
+extern "C" uint32_t kv_vmm_lent(const kv_vmm_pool* pool) { return pool ? (uint32_t)pool->lent.size() : 0u; }
 
 extern "C" int kv_vmm_restore(kv_vmm_pool* pool) {
   if (pool == nullptr) return KV_E_NULL;
-  int rc = hip_rc(hipDeviceSynchronize());
+  const int rc = hip_rc(hipDeviceSynchronize());
   if (rc != KV_OK) return rc;
-  const uint64_t bb = pool->block_bytes;
-  while (!pool->lent.empty()) {
-    const size_t k = pool->lent.size() - 1;
-    const uint32_t id = (uint32_t)pool->lent[k];
-    if (hipMemUnmap(pool->slot_base + (uint64_t)k * bb, bb) != hipSuccess) return KV_E_HIP;
-    pool->lent.pop_back();
-    if (hipMemMap(pool->kv_base + (uint64_t)id * bb, bb, 0, pool->handles[id], 0) != hipSuccess) return KV_E_HIP;
-    pool->in_kv[id] = 1;
-    rc = grant(pool->kv_base + (uint64_t)id * bb, bb, pool->device);
-    if (rc != KV_OK) return rc;
-  }
-  return KV_OK;
+  return give_back(pool, 0);
 }

@@ -447,7 +447,7 @@ def test_pipelined_materialize_matches_oracle(oracle):
         assert np.array_equal(pool_dev.cpu().numpy(), want), f"early_bytes={early_bytes}"
 
 
-def test_vmm_variant_lends_pages_without_moving_bytes():
+def test_vmm_variant_lends_pages_without_moving_bytes(oracle):
     """The no-move variant: pages of unused blocks appear back to back in the slot range,
     live KV is untouched, weights written through the slot land in those pages, and a
     restore puts every page back under its block."""
@@ -469,9 +469,12 @@ def test_vmm_variant_lends_pages_without_moving_bytes():
         with pytest.raises(wk.WarmKVError) as e:
             wk.kv_vmm_reclaim(pool, live, free_desc.size + 1)
         assert e.value.code == wk.KV_E_NOSPACE
+        assert oracle.vmm_select(live, nb, free_desc.size + 1) is None
+        assert wk.kv_vmm_lent(pool) == 0
         want = 40
         ids = wk.kv_vmm_reclaim(pool, live, want)
-        assert ids == free_desc[:want].tolist()
+        assert ids == oracle.vmm_select(live, nb, want).tolist()      # the oracle's page choice, in slot order
+        assert wk.kv_vmm_lent(pool) == want
         kv = gh.view_device(kv_ptr, nb * bb)
         slot = gh.view_device(slot_ptr, want * bb)
         expect = torch.empty(bb, dtype=torch.uint8, device=gh.dev())
@@ -503,8 +506,46 @@ def test_vmm_variant_lends_pages_without_moving_bytes():
         k = 3                                            # a returned page still holds the weight bytes written to it
         assert torch.equal(kv[ids[k] * bb:(ids[k] + 1) * bb].cpu(), weights[k * bb:(k + 1) * bb])
         ids2 = wk.kv_vmm_reclaim(pool, live, 5)          # and the pool can lend again
-        assert ids2 == ids[:5]
+        assert ids2 == oracle.vmm_select(live, nb, 5).tolist()
         wk.kv_vmm_restore(pool)
+        assert wk.kv_vmm_lent(pool) == 0
+
+        # the same hand-over with the weight stream pipelined behind the mapping, chunk by chunk:
+        # the slot must hold what the oracle's weight copy puts into a host buffer of the same size
+        content.fill_device(kv_ptr, nb, bb, seed)
+        want = 37
+        sizes = [5 * bb + 4096, 256, 0, 11 * bb - 8192, 3 * bb // 2]
+        offs = [bb // 2, 6 * bb, 6 * bb + 512, 7 * bb, 20 * bb + 256]      # unordered in time: listed shuffled below
+        hosts = []
+        for i, sz in enumerate(sizes):
+            t = torch.empty(max(sz, 8), dtype=torch.uint8, pin_memory=True)
+            t.numpy()[:sz] = content.item_bytes_host(9, i, (sz + 7) // 8 * 8, None)[:sz]
+            hosts.append(t)
+        listed = [3, 0, 4, 2, 1]
+        copy_stream = torch.cuda.Stream()
+        for chunk in (4, 0, 1000):
+            with pytest.raises(wk.WarmKVError) as e:     # an extent past the slot prefix: refused before anything changes
+                wk.kv_vmm_reclaim_load(pool, live, want, [(hosts[0], bb, want * bb - 16)], copy_stream.cuda_stream, chunk)
+            assert e.value.code == wk.KV_E_TOOBIG and wk.kv_vmm_lent(pool) == 0
+            with pytest.raises(wk.WarmKVError) as e:
+                wk.kv_vmm_reclaim_load(pool, live, want, [(hosts[0], bb, 0), (hosts[3], bb, bb - 16)],
+                                       copy_stream.cuda_stream, chunk)
+            assert e.value.code == wk.KV_E_OVERLAP and wk.kv_vmm_lent(pool) == 0
+            ids3 = wk.kv_vmm_reclaim_load(pool, live, want, [(hosts[i], sizes[i], offs[i]) for i in listed],
+                                          copy_stream.cuda_stream, chunk)
+            torch.cuda.synchronize()
+            assert ids3 == oracle.vmm_select(live, nb, want).tolist()
+            expect_slot = np.empty(want * bb, dtype=np.uint8)
+            content.fill_host(expect_slot, bb, ids3, seed, None)           # the pages' old bytes, in slot order
+            assert oracle.materialize(expect_slot, 0, [(hosts[i].numpy()[:sizes[i]], offs[i]) for i in listed]) == 0
+            slot = gh.view_device(slot_ptr, want * bb)
+            assert np.array_equal(slot.cpu().numpy(), expect_slot), f"chunk_blocks={chunk}"
+            for i in np.flatnonzero(live_bits).tolist()[::7]:
+                check_block(kv, i, i)
+            del slot
+            wk.kv_vmm_restore(pool)
+            content.fill_device(kv_ptr, nb, bb, seed)
+            torch.cuda.synchronize()
         del kv
     finally:
         torch.cuda.synchronize()

@@ -328,6 +328,53 @@ def test_grow_hand_cases_and_byte_brute_force(oracle):
         assert n == int(ev.sum())
 
 
+def _check_vmm_selection(live, want, ids):
+    """Properties that fix the selection uniquely: `want` distinct unused blocks, highest first, and
+    no unused block left out is higher than one that was taken."""
+    ids = np.asarray(ids, dtype=np.int64)
+    assert ids.shape == (want,)
+    assert not live[ids].any(), "only unused blocks lend pages"
+    assert np.all(np.diff(ids) < 0), "highest first, no block twice"
+    if want:
+        left_out = np.setdiff1d(np.flatnonzero(~live), ids)
+        assert left_out.size == 0 or left_out.max() < ids.min(), "the highest free ids are the ones taken"
+
+
+def test_vmm_select_fixtures_and_exhaustive(oracle):
+    with open(os.path.join(GOLDEN, "vmm_select_handworked.json")) as f:
+        cases = json.load(f)["cases"]
+    for c in cases:
+        words = _words(c["live_words_hex"])
+        clean = bitmap_from_ids(c["live_ids"], c["num_blocks"])
+        valid = np.uint64((1 << (c["num_blocks"] % 64)) - 1) if c["num_blocks"] % 64 else np.uint64(0xFFFFFFFFFFFFFFFF)
+        assert np.array_equal(words[:-1], clean[:-1]) and (words[-1] & valid) == clean[-1], c["name"]
+        got = oracle.vmm_select(words, c["num_blocks"], c["want"])
+        if c["ids"] is None:
+            assert got is None, c["name"]
+        else:
+            assert got.tolist() == c["ids"], c["name"]
+    # every bitmap of up to 10 blocks, every request size
+    for nb in range(0, 11):
+        for bits in range(1 << nb):
+            live = np.array([(bits >> i) & 1 for i in range(nb)], dtype=bool)
+            words = bitmap_from_ids(np.flatnonzero(live), nb)
+            n_free = int((~live).sum())
+            for want in range(0, nb + 2):
+                got = oracle.vmm_select(words, nb, want)
+                if want > n_free:
+                    assert got is None
+                else:
+                    _check_vmm_selection(live, want, got)
+    # the property check itself rejects the plausible mistakes
+    live = np.array([0, 1, 0, 0, 1, 1, 0, 0, 0, 1], dtype=bool)
+    good = oracle.vmm_select(bitmap_from_ids(np.flatnonzero(live), 10), 10, 3)
+    for name, bad in {"ascending": good[::-1], "lowest free ids": np.array([3, 2, 0]), "a live block": np.array([9, 8, 7]),
+                      "skipped one": np.array([8, 6, 3]), "twice": np.array([8, 8, 7])}.items():
+        with pytest.raises(AssertionError):
+            _check_vmm_selection(live, 3, bad)
+            pytest.fail(f"mutant accepted: {name}")
+
+
 # ----------------------------------------------------------------- mutants
 class _Mut:
     def __init__(self, p, **kw):

@@ -201,7 +201,12 @@ typedef struct wm_tensor {
  * wait, the caller has ordered the streams) and enqueue the host-to-device
  * copies in chunks.  The region still holds moving blocks until kv_compact has
  * read them, hence the event.  tensors [host] may be freed on return; the
- * host_ptr buffers must stay valid until copy_stream has drained. */
+ * host_ptr buffers must stay valid until copy_stream has drained.
+ * WARNING: this call knows nothing of the plan.  If the plan was infeasible
+ * (KV_E_NOSPACE), kv_compact and kv_remap_tables did nothing and the region
+ * still holds the live blocks that could not move: a weight stream enqueued
+ * behind them overwrites running requests' KV.  Read the verdict first
+ * (kv_plan_fetch) or use kv_switch, which does and sends nothing then. */
 int weights_materialize(const kv_pool_desc* pool, uint32_t boundary,
                         const wm_tensor* tensors, uint32_t n_tensors,
                         void* copy_stream, void* compaction_done);
@@ -223,7 +228,8 @@ typedef struct wm_piece {
  * at block boundaries; runs that lie wholly in free blocks become early pieces
  * until early_bytes (0 = 128 MiB) have been collected; all other bytes become
  * late pieces, one per tensor remainder run.  Host arithmetic only.
- * Block-major pools only (KV_E_RANGE otherwise).
+ * In a layer-major pool the unit is a block's tile in one strip: region offset
+ * x lies in the tile of block boundary + (x mod strip bytes) / tile_bytes.
  * Writes at most `capacity` pieces to out [host] (early pieces first) and the
  * full count to *n_out; returns KV_E_TOOBIG if capacity is too small, and the
  * validation errors of weights_materialize. */
@@ -249,6 +255,14 @@ int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t boundary,
 int kv_compact_moves(const kv_pool_desc* pool, const kv_plan* plan, uint32_t first_move,
                      uint32_t max_moves, void* stream);
 
+/* Block copy of a part of every move: only the tiles of layers [first_layer,
+ * first_layer + max_layers) that exist; otherwise as kv_compact.  In a
+ * layer-major pool that is the slabs of those layers, so "the first f layers"
+ * evacuate the first f strips of the reclaimed space, which is the order region
+ * offsets count in. */
+int kv_compact_layers(const kv_pool_desc* pool, const kv_plan* plan, uint32_t first_layer,
+                      uint32_t max_layers, void* stream);
+
 /* Number of live blocks among the first front_blocks blocks at and above
  * `boundary` in live_host [host bitmap, as given to kv_plan_reclaim]: how many
  * moves of a feasible plan evacuate that front.  Host arithmetic only. */
@@ -262,8 +276,12 @@ uint32_t kv_movers_in_front(const uint64_t* live_host, uint32_t num_blocks, uint
  * kv_movers_in_front(.., ceil(front_bytes / block_bytes))) and the remaining
  * bytes behind compaction_done (recorded after the rest of the block copy).
  * Either event may be NULL (no wait).  Same validation, same bytes in the pool
- * as weights_materialize; each tensor is cut at most once.  Block-major pools
- * only (KV_E_RANGE otherwise). */
+ * as weights_materialize; each tensor is cut at most once.
+ * In a layer-major pool region offsets count strip by strip, and the region
+ * becomes ready strip by strip when the block copy takes the slabs in layer
+ * order: front_done is then recorded after kv_compact_layers(0, f) with
+ * f = ceil(front_bytes / strip bytes), compaction_done after
+ * kv_compact_layers(f, all the rest). */
 int weights_materialize_front(const kv_pool_desc* pool, uint32_t boundary, uint64_t front_bytes,
                               const wm_tensor* tensors, uint32_t n_tensors,
                               void* copy_stream, void* front_done, void* compaction_done);
@@ -291,12 +309,14 @@ typedef struct kv_switch_request {
 
 /* The hand-over as one call: plan, block copy and table rewrite on
  * compute_stream, the weight stream on copy_stream behind compaction_done.
- * If live_host is given and the pool is block-major the weight stream is
+ * If live_host is given the weight stream is
  * pipelined with the block copy: front first if front_done is given too (the
  * block copy is launched in two parts, the movers under the first early_bytes
  * of the region and the rest, with front_done recorded in between; early_bytes
  * 0 = sized from the plan so that the link stays busy until the block copy has
- * ended), else block by block as in weights_materialize_pipelined.  Existing requests take precedence over prewarmed weights
+ * ended; in a layer-major pool the front is a whole number of strips and the
+ * two parts are layer ranges), else block by block as in
+ * weights_materialize_pipelined.  Existing requests take precedence over prewarmed weights
  * (Sec. 3.3): after the planner has run, compute_stream is synchronised once
  * and its verdict read; if the request is infeasible the call returns
  * KV_E_NOSPACE and nothing else is enqueued - no pool byte, table entry or
@@ -324,8 +344,10 @@ int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blocks,
  * weights_materialize relative to the old region: evicted[i] = 1 if it has a
  * byte inside the returned blocks (it is lost), else 0 and new_offset[i] is its
  * offset relative to the new region's start.  Host arithmetic only; evicted,
- * new_offset [host] have n_tensors entries.  Block-major pools only
- * (KV_E_RANGE otherwise).  Returns the number of evicted
+ * new_offset [host] have n_tensors entries.  In a layer-major pool every
+ * strip loses its first (new - old) tiles: a tensor is lost if it has a byte
+ * in them, and a survivor's new offset counts through the shorter strips.
+ * Returns the number of evicted
  * tensors, or KV_E_RANGE / KV_E_NULL / KV_E_TOOBIG (an extent outside the
  * old region). */
 int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint32_t new_boundary,

@@ -68,6 +68,8 @@ def lib():
         L.oracle_grow.argtypes = [u64, u32, u32, u32, ctypes.POINTER(_Tensor), u32, vp, vp]
         L.oracle_reserve_blocks.restype = ctypes.c_int64
         L.oracle_reserve_blocks.argtypes = [u64, u64, u32, u32]
+        L.oracle_grow_strips.restype = ctypes.c_int64
+        L.oracle_grow_strips.argtypes = [u64, u32, u32, u64, u32, u32, ctypes.POINTER(_Tensor), u32, vp, vp]
         L.oracle_vmm_select.restype = ctypes.c_int
         L.oracle_vmm_select.argtypes = [vp, u32, u32, vp]
         _lib = L
@@ -188,6 +190,22 @@ def grow(block_bytes: int, num_blocks: int, old_boundary: int, new_boundary: int
     ev = np.zeros(max(1, len(extents)), dtype=np.uint8)
     no = np.zeros(max(1, len(extents)), dtype=np.uint64)
     rc = int(lib().oracle_grow(block_bytes, num_blocks, old_boundary, new_boundary, arr, len(extents), _p(ev), _p(no)))
+    if rc < 0:
+        return rc, None, None
+    return rc, ev[:len(extents)], no[:len(extents)]
+
+
+def grow_strips(tile_bytes: int, num_layers: int, num_blocks: int, layer_stride: int, old_boundary: int,
+                new_boundary: int, extents):
+    """Reverse switch in a layer-major pool; arguments and result as for :func:`grow`."""
+    extents = list(extents)
+    arr = (_Tensor * max(1, len(extents)))()
+    for i, (nbytes, off) in enumerate(extents):
+        arr[i] = _Tensor(None, nbytes, off)
+    ev = np.zeros(max(1, len(extents)), dtype=np.uint8)
+    no = np.zeros(max(1, len(extents)), dtype=np.uint64)
+    rc = int(lib().oracle_grow_strips(tile_bytes, num_layers, num_blocks, layer_stride, old_boundary, new_boundary,
+                                      arr, len(extents), _p(ev), _p(no)))
     if rc < 0:
         return rc, None, None
     return rc, ev[:len(extents)], no[:len(extents)]

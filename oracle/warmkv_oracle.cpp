@@ -232,6 +232,45 @@ int64_t oracle_grow(uint64_t block_bytes, uint32_t num_blocks, uint32_t old_boun
   return lost;
 }
 
+// Reverse switch in a layer-major pool.  The reclaimed space is one strip per layer slab, slab
+// bytes [boundary*tile_bytes, num_blocks*tile_bytes); region offsets count through strip 0, strip
+// 1, ...  Each tensor is placed at its absolute pool byte range under the old boundary; it is lost
+// if that range meets a returned tile range [old_boundary*tile_bytes, new_boundary*tile_bytes) of
+// its slab; a survivor's new offset is the region offset of the same absolute byte under the new
+// boundary.  (An empty extent at the very end of the region counts as the end of the last strip.)
+int64_t oracle_grow_strips(uint64_t tile_bytes, uint32_t num_layers, uint32_t num_blocks,
+                           uint64_t layer_stride, uint32_t old_boundary, uint32_t new_boundary,
+                           const oracle_tensor* tensors, uint32_t n_tensors, uint8_t* evicted,
+                           uint64_t* new_offset) {
+  if (n_tensors && (!tensors || !evicted || !new_offset)) return ORACLE_E_NULL;
+  if (old_boundary > new_boundary || new_boundary > num_blocks) return ORACLE_E_RANGE;
+  const uint64_t old_strip = (uint64_t)(num_blocks - old_boundary) * tile_bytes;
+  const uint64_t new_strip = (uint64_t)(num_blocks - new_boundary) * tile_bytes;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const oracle_tensor& t = tensors[i];
+    if (t.dst_offset > old_strip * num_layers || t.bytes > old_strip * num_layers - t.dst_offset)
+      return ORACLE_E_TOOBIG;
+    if (t.bytes && t.dst_offset / old_strip != (t.dst_offset + t.bytes - 1) / old_strip) return ORACLE_E_TOOBIG;
+  }
+  int64_t lost = 0;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const oracle_tensor& t = tensors[i];
+    uint64_t layer = old_strip ? t.dst_offset / old_strip : 0;
+    if (layer == num_layers && layer > 0) layer = num_layers - 1;
+    const uint64_t slab = layer * layer_stride;
+    // absolute pool bytes [lo, hi) of the tensor; returned bytes [back_lo, back_hi) of its slab
+    const uint64_t lo = slab + (uint64_t)old_boundary * tile_bytes + (t.dst_offset - layer * old_strip);
+    const uint64_t hi = lo + t.bytes;
+    const uint64_t back_lo = slab + (uint64_t)old_boundary * tile_bytes;
+    const uint64_t back_hi = slab + (uint64_t)new_boundary * tile_bytes;
+    const bool overlaps = lo < hi && lo < back_hi && back_lo < hi;
+    evicted[i] = overlaps;
+    new_offset[i] = (!overlaps && lo >= back_hi) ? layer * new_strip + (lo - back_hi) : 0;
+    lost += overlaps;
+  }
+  return lost;
+}
+
 // No-move variant (Sec. 3.4; App. C, Fig. 4b steps 1-2): which unused blocks lend their physical
 // pages to the new model's slot.  Any `want` unused blocks would do for the paper; the reading
 // taken is "the `want` highest free ids, highest first", which keeps the low ids for the running

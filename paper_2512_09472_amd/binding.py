@@ -34,7 +34,7 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
-           "weights_materialize_pipelined", "kv_compact_moves", "kv_movers_in_front", "weights_materialize_front",
+           "weights_materialize_pipelined", "kv_compact_moves", "kv_compact_layers", "kv_movers_in_front", "weights_materialize_front",
            "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_reclaim_load", "kv_vmm_lent", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
            "ws_place_replicas", "warmkv_version", "warmkv_build_id")
@@ -166,6 +166,8 @@ def load():
                                                 c_uint64, c_void_p, c_void_p]
     L.kv_compact_moves.restype = c_int
     L.kv_compact_moves.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), c_uint32, c_uint32, c_void_p]
+    L.kv_compact_layers.restype = c_int
+    L.kv_compact_layers.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), c_uint32, c_uint32, c_void_p]
     L.kv_movers_in_front.restype = c_uint32
     L.kv_movers_in_front.argtypes = [c_void_p, c_uint32, c_uint32, c_uint32]
     L.weights_materialize_front.restype = c_int
@@ -305,6 +307,11 @@ def weights_materialize_pipelined(pool: kv_pool_desc, boundary: int, live_host, 
 
 def kv_compact_moves(pool: kv_pool_desc, plan: kv_plan, first_move: int, max_moves: int, stream=0) -> None:
     _check("kv_compact_moves", load().kv_compact_moves(byref(pool), byref(plan), first_move, max_moves, _ptr(stream)))
+
+
+def kv_compact_layers(pool: kv_pool_desc, plan: kv_plan, first_layer: int, max_layers: int, stream=0) -> None:
+    _check("kv_compact_layers", load().kv_compact_layers(byref(pool), byref(plan), first_layer, max_layers,
+                                                          _ptr(stream)))
 
 
 def kv_movers_in_front(live_host, num_blocks: int, boundary: int, front_blocks: int) -> int:

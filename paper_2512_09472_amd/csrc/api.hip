@@ -75,25 +75,41 @@ extern "C" int64_t kv_reserve_blocks(uint64_t capacity_blocks, uint64_t used_blo
 }
 
 // Sec. 3.3, last sentence: weights are evicted when the reserve runs short.
+// Region offsets count through the reclaimed space: one byte range in a
+// block-major pool (one "strip"), L strips taken in layer order in a
+// layer-major pool.  Raising the boundary takes the first returned_per_strip
+// bytes of every strip away.
 extern "C" int64_t kv_grow(const kv_pool_desc* pool, uint32_t old_boundary, uint32_t new_boundary,
                            const wm_tensor* tensors, uint32_t n_tensors, uint8_t* evicted,
                            uint64_t* new_offset) {
   if (pool == nullptr) return KV_E_NULL;
   if (n_tensors != 0 && (tensors == nullptr || evicted == nullptr || new_offset == nullptr)) return KV_E_NULL;
   if (old_boundary > new_boundary || new_boundary > pool->num_blocks) return KV_E_RANGE;
-  if (pool->layer_stride_bytes != 0) return KV_E_RANGE;  // block-major pools only
   if ((pool->tile_bytes != 0 && pool->num_layers != 0) && !pool_extent_ok(*pool)) return KV_E_RANGE;
-  const uint64_t block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
-  const uint64_t old_region = (uint64_t)(pool->num_blocks - old_boundary) * block_bytes;
-  const uint64_t returned = (uint64_t)(new_boundary - old_boundary) * block_bytes;
-  for (uint32_t i = 0; i < n_tensors; ++i)
-    if (tensors[i].dst_offset > old_region || tensors[i].bytes > old_region - tensors[i].dst_offset)
-      return KV_E_TOOBIG;
+  const bool layer_major = pool->layer_stride_bytes != 0;
+  const uint64_t per_block = layer_major ? pool->tile_bytes : (uint64_t)pool->num_layers * pool->tile_bytes;
+  const uint64_t strips = layer_major ? pool->num_layers : 1u;
+  const uint64_t old_strip = (uint64_t)(pool->num_blocks - old_boundary) * per_block;
+  const uint64_t new_strip = (uint64_t)(pool->num_blocks - new_boundary) * per_block;
+  const uint64_t returned = (uint64_t)(new_boundary - old_boundary) * per_block;  // per strip, at its start
+  const uint64_t old_region = old_strip * strips;
+  for (uint32_t i = 0; i < n_tensors; ++i) {
+    const wm_tensor& t = tensors[i];
+    if (t.dst_offset > old_region || t.bytes > old_region - t.dst_offset) return KV_E_TOOBIG;
+    if (t.bytes != 0 && t.dst_offset % old_strip + t.bytes > old_strip) return KV_E_TOOBIG;  // straddles two strips
+  }
   int64_t lost = 0;
   for (uint32_t i = 0; i < n_tensors; ++i) {
-    const bool hit = tensors[i].bytes != 0 && tensors[i].dst_offset < returned;
+    const wm_tensor& t = tensors[i];
+    uint64_t strip = old_strip ? t.dst_offset / old_strip : 0;
+    uint64_t within = old_strip ? t.dst_offset % old_strip : 0;
+    if (strip == strips && strip != 0) {  // an empty extent at the very end of the region
+      strip = strips - 1;
+      within = old_strip;
+    }
+    const bool hit = t.bytes != 0 && within < returned;
     evicted[i] = hit ? 1 : 0;
-    new_offset[i] = hit ? 0 : (tensors[i].dst_offset >= returned ? tensors[i].dst_offset - returned : 0);
+    new_offset[i] = (!hit && within >= returned) ? strip * new_strip + (within - returned) : 0;
     lost += hit;
   }
   return lost;

@@ -421,8 +421,10 @@ using namespace warmkv;
 
 namespace {
 
+// Copies the tiles of layers [layer_first, layer_first + layer_count) (clipped to the pool's layers)
+// of moves [move_first, move_first + move_count) (clipped to the plan's moves on the device).
 int launch_copy(const kv_pool_desc* pool, const kv_plan* plan, const kv_compact_tuning* tuning,
-                uint32_t move_first, uint32_t move_count, void* stream) {
+                uint32_t move_first, uint32_t move_count, uint32_t layer_first, uint32_t layer_count, void* stream) {
   if (pool == nullptr || plan == nullptr || plan->state == nullptr) return KV_E_NULL;
   if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
   if (!pool_extent_ok(*pool)) return KV_E_RANGE;  // zero or absurd sizes
@@ -444,21 +446,24 @@ int launch_copy(const kv_pool_desc* pool, const kv_plan* plan, const kv_compact_
     return KV_E_RANGE;
   if (plan->capacity == 0 || pool->num_blocks == 0) return KV_OK;  // nothing can move
   if (move_first >= plan->capacity || move_count == 0) return KV_OK;   // no such moves
+  if (layer_first >= pool->num_layers || layer_count == 0) return KV_OK;  // no such layers
+  if (layer_count > pool->num_layers - layer_first) layer_count = pool->num_layers - layer_first;
   if (pool->base == nullptr || plan->src == nullptr || plan->dst == nullptr) return KV_E_NULL;
   if (((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
 
   CopyArgs a;
-  a.base = (uint8_t*)pool->base;
-  if (layer_major) {
+  if (layer_major) {  // one segment (tile) per chosen layer slab
+    a.base = (uint8_t*)pool->base + (uint64_t)layer_first * pool->layer_stride_bytes;
     a.block_stride = pool->tile_bytes;
     a.seg_stride = pool->layer_stride_bytes;
     a.seg_bytes = pool->tile_bytes;
-  } else {
+  } else {            // the chosen layers' tiles are one contiguous run inside the block
+    a.base = (uint8_t*)pool->base + (uint64_t)layer_first * pool->tile_bytes;
     a.block_stride = (uint64_t)pool->num_layers * pool->tile_bytes;
     a.seg_stride = 0;
-    a.seg_bytes = a.block_stride;
+    a.seg_bytes = (uint64_t)layer_count * pool->tile_bytes;
   }
-  const uint64_t segs = layer_major ? pool->num_layers : 1u;
+  const uint64_t segs = layer_major ? layer_count : 1u;
   // Default units are 64 KiB, the last one of a segment shorter.  A short unit costs a whole
   // ticket, and tickets of 40 KiB or less on average are drawn faster than one counter address
   // can hand them out, so small ragged segments (up to four units) are cut differently where
@@ -542,14 +547,19 @@ int launch_copy(const kv_pool_desc* pool, const kv_plan* plan, const kv_compact_
 
 extern "C" int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
                                  const kv_compact_tuning* tuning, void* stream) {
-  return launch_copy(pool, plan, tuning, 0u, ~0u, stream);
+  return launch_copy(pool, plan, tuning, 0u, ~0u, 0u, ~0u, stream);
 }
 
 extern "C" int kv_compact(const kv_pool_desc* pool, const kv_plan* plan, void* stream) {
-  return launch_copy(pool, plan, nullptr, 0u, ~0u, stream);
+  return launch_copy(pool, plan, nullptr, 0u, ~0u, 0u, ~0u, stream);
 }
 
 extern "C" int kv_compact_moves(const kv_pool_desc* pool, const kv_plan* plan, uint32_t first_move,
                                 uint32_t max_moves, void* stream) {
-  return launch_copy(pool, plan, nullptr, first_move, max_moves, stream);
+  return launch_copy(pool, plan, nullptr, first_move, max_moves, 0u, ~0u, stream);
+}
+
+extern "C" int kv_compact_layers(const kv_pool_desc* pool, const kv_plan* plan, uint32_t first_layer,
+                                 uint32_t max_layers, void* stream) {
+  return launch_copy(pool, plan, nullptr, 0u, ~0u, first_layer, max_layers, stream);
 }

@@ -30,6 +30,7 @@ struct Region {
   uint64_t bytes;         // size of the region (all strips together)
   uint64_t strip_bytes;   // layer-major: bytes per strip
   uint64_t layer_stride;
+  uint64_t tile_bytes;
 };
 
 // Device address of region offset `at` (validated to lie inside the region).
@@ -50,6 +51,7 @@ int validate(const kv_pool_desc* pool, uint32_t boundary, const wm_tensor* tenso
   region->layer_major = pool->layer_stride_bytes != 0;
   region->layer_stride = pool->layer_stride_bytes;
   region->block_bytes = (uint64_t)pool->num_layers * pool->tile_bytes;
+  region->tile_bytes = pool->tile_bytes;
   if (region->layer_major) {
     if (pool->layer_stride_bytes < (uint64_t)pool->num_blocks * pool->tile_bytes) return KV_E_RANGE;
     region->offset = (uint64_t)boundary * pool->tile_bytes;
@@ -126,25 +128,31 @@ inline bool was_live(const uint64_t* live, uint64_t block) { return (live[block 
 
 // Cut the tensors at block boundaries into early pieces (runs of blocks that
 // were free before the move, while the early budget lasts) and late pieces.
+// In a layer-major pool the unit is a block's tile in one strip: region offset
+// `at` lies in strip at / strip_bytes, in the tile of block boundary +
+// (at % strip_bytes) / tile_bytes (strips are whole tiles, and a tensor never
+// leaves its strip).
 void schedule(const Region& r, uint32_t boundary, const uint64_t* live, const wm_tensor* tensors,
               uint32_t n_tensors, uint64_t early_budget, std::vector<wm_piece>* early,
               std::vector<wm_piece>* late) {
+  const uint64_t unit = r.layer_major ? r.tile_bytes : r.block_bytes;
+  auto block_of = [&](uint64_t at) -> uint64_t {
+    return boundary + (r.layer_major ? (at % r.strip_bytes) / unit : at / unit);
+  };
   uint64_t early_total = 0;
   for (uint32_t i = 0; i < n_tensors; ++i) {
     const wm_tensor& t = tensors[i];
     uint64_t pos = 0;  // bytes of this tensor already assigned
     while (pos < t.bytes) {
       const uint64_t at = t.dst_offset + pos;
-      const uint64_t block = boundary + at / r.block_bytes;
-      const bool ready = early_total < early_budget && !was_live(live, block);
+      const bool ready = early_total < early_budget && !was_live(live, block_of(at));
       // extend over following blocks of the same kind
-      uint64_t end = std::min(t.bytes, pos + (r.block_bytes - at % r.block_bytes));
+      uint64_t end = std::min(t.bytes, pos + (unit - at % unit));
       uint64_t collected = early_total + (ready ? end - pos : 0);
       while (end < t.bytes) {
-        const uint64_t next_block = boundary + (t.dst_offset + end) / r.block_bytes;
-        const bool next_ready = collected < early_budget && !was_live(live, next_block);
+        const bool next_ready = collected < early_budget && !was_live(live, block_of(t.dst_offset + end));
         if (next_ready != ready) break;
-        const uint64_t next_end = std::min(t.bytes, end + r.block_bytes);
+        const uint64_t next_end = std::min(t.bytes, end + unit);
         if (ready) collected += next_end - end;
         end = next_end;
       }
@@ -198,7 +206,7 @@ extern "C" int weights_materialize_schedule(const kv_pool_desc* pool, uint32_t b
     if (rc != KV_OK) return rc;
     if (n_out == nullptr || (capacity != 0 && out == nullptr)) return KV_E_NULL;
     if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
-    if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
+    if (r.block_bytes == 0) return KV_E_RANGE;
     std::vector<wm_piece> early, late;
     schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
     const size_t total = early.size() + late.size();
@@ -220,14 +228,14 @@ extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t 
     int rc = validate(pool, boundary, tensors, n_tensors, &r);
     if (rc != KV_OK) return rc;
     if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
-    if (r.block_bytes == 0 || r.layer_major) return KV_E_RANGE;
+    if (r.block_bytes == 0) return KV_E_RANGE;
     std::vector<wm_piece> early, late;
     schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
     hipStream_t s = (hipStream_t)copy_stream;
-    uint8_t* region = (uint8_t*)pool->base + r.offset;
     Requests requests(s);
     for (const wm_piece& p : early) {
-      rc = requests.add(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes);
+      rc = requests.add(region_address(pool, r, p.dst_offset), (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset,
+                        p.bytes);
       if (rc != KV_OK) return rc;
     }
     rc = requests.flush();
@@ -237,7 +245,8 @@ extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t 
       if (rc != KV_OK) return rc;
     }
     for (const wm_piece& p : late) {
-      rc = requests.add(region + p.dst_offset, (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset, p.bytes);
+      rc = requests.add(region_address(pool, r, p.dst_offset), (const uint8_t*)tensors[p.tensor].host_ptr + p.src_offset,
+                        p.bytes);
       if (rc != KV_OK) return rc;
     }
     return requests.flush();
@@ -265,9 +274,7 @@ extern "C" int weights_materialize_front(const kv_pool_desc* pool, uint32_t boun
     Region r;
     int rc = validate(pool, boundary, tensors, n_tensors, &r);
     if (rc != KV_OK) return rc;
-    if (r.layer_major) return KV_E_RANGE;
     hipStream_t s = (hipStream_t)copy_stream;
-    uint8_t* region = (uint8_t*)pool->base + r.offset;
     auto front_part = [&](const wm_tensor& t) -> uint64_t {  // leading bytes of t that lie below the mark
       return t.dst_offset >= front_bytes ? 0 : std::min(t.bytes, front_bytes - t.dst_offset);
     };
@@ -277,7 +284,9 @@ extern "C" int weights_materialize_front(const kv_pool_desc* pool, uint32_t boun
     }
     Requests requests(s);
     for (uint32_t i = 0; i < n_tensors; ++i) {
-      rc = requests.add(region + tensors[i].dst_offset, (const uint8_t*)tensors[i].host_ptr, front_part(tensors[i]));
+      if (tensors[i].bytes == 0) continue;
+      rc = requests.add(region_address(pool, r, tensors[i].dst_offset), (const uint8_t*)tensors[i].host_ptr,
+                        front_part(tensors[i]));
       if (rc != KV_OK) return rc;
     }
     rc = requests.flush();
@@ -288,7 +297,8 @@ extern "C" int weights_materialize_front(const kv_pool_desc* pool, uint32_t boun
     }
     for (uint32_t i = 0; i < n_tensors; ++i) {
       const uint64_t head = front_part(tensors[i]);
-      rc = requests.add(region + tensors[i].dst_offset + head, (const uint8_t*)tensors[i].host_ptr + head,
+      if (head == tensors[i].bytes) continue;
+      rc = requests.add(region_address(pool, r, tensors[i].dst_offset + head), (const uint8_t*)tensors[i].host_ptr + head,
                         tensors[i].bytes - head);
       if (rc != KV_OK) return rc;
     }
@@ -325,7 +335,7 @@ extern "C" int kv_switch(const kv_switch_request* rq, kv_plan_state* result) {
     if (result != nullptr) *result = st;
     if (st.status != KV_OK) return st.status;  // running requests keep their blocks; no weight byte is sent
   
-    const bool can_pipeline = rq->live_host != nullptr && !r.layer_major && r.block_bytes != 0;
+    const bool can_pipeline = rq->live_host != nullptr && r.block_bytes != 0 && r.bytes != 0;
     const bool front_first = can_pipeline && rq->front_done != nullptr && rq->n_tensors != 0;
     uint64_t front_bytes = 0;
     if (front_first) {
@@ -333,15 +343,27 @@ extern "C" int kv_switch(const kv_switch_request* rq, kv_plan_state* result) {
       // the link carries roughly 1/120 of what the block copy moves in the same time; twice that.
       const uint64_t moved = 2ull * st.n_moves * r.block_bytes;
       front_bytes = rq->early_bytes ? rq->early_bytes : std::max<uint64_t>(64ull << 20, moved / 64);
-      const uint64_t front_blocks =
-          std::min<uint64_t>((front_bytes + r.block_bytes - 1) / r.block_bytes, pool->num_blocks - plan->boundary);
-      front_bytes = front_blocks * r.block_bytes;
-      const uint32_t head = kv_movers_in_front(rq->live_host, pool->num_blocks, plan->boundary, (uint32_t)front_blocks);
-      rc = kv_compact_moves(pool, plan, 0u, head, rq->compute_stream);
-      if (rc != KV_OK) return rc;
-      rc = hip_rc(hipEventRecord((hipEvent_t)rq->front_done, (hipStream_t)rq->compute_stream));
-      if (rc != KV_OK) return rc;
-      rc = kv_compact_moves(pool, plan, head, ~0u, rq->compute_stream);
+      if (r.layer_major) {
+        // The block copy walks the slabs in layer order, so the region (strip 0, strip 1, ...) is
+        // ready strip by strip: the front is a whole number of strips.
+        const uint64_t front_strips = std::min<uint64_t>((front_bytes + r.strip_bytes - 1) / r.strip_bytes, pool->num_layers);
+        front_bytes = front_strips * r.strip_bytes;
+        rc = kv_compact_layers(pool, plan, 0u, (uint32_t)front_strips, rq->compute_stream);
+        if (rc != KV_OK) return rc;
+        rc = hip_rc(hipEventRecord((hipEvent_t)rq->front_done, (hipStream_t)rq->compute_stream));
+        if (rc != KV_OK) return rc;
+        rc = kv_compact_layers(pool, plan, (uint32_t)front_strips, ~0u, rq->compute_stream);
+      } else {
+        const uint64_t front_blocks =
+            std::min<uint64_t>((front_bytes + r.block_bytes - 1) / r.block_bytes, pool->num_blocks - plan->boundary);
+        front_bytes = front_blocks * r.block_bytes;
+        const uint32_t head = kv_movers_in_front(rq->live_host, pool->num_blocks, plan->boundary, (uint32_t)front_blocks);
+        rc = kv_compact_moves(pool, plan, 0u, head, rq->compute_stream);
+        if (rc != KV_OK) return rc;
+        rc = hip_rc(hipEventRecord((hipEvent_t)rq->front_done, (hipStream_t)rq->compute_stream));
+        if (rc != KV_OK) return rc;
+        rc = kv_compact_moves(pool, plan, head, ~0u, rq->compute_stream);
+      }
     } else {
       rc = kv_compact(pool, plan, rq->compute_stream);
     }

@@ -195,6 +195,67 @@ def test_materialize_schedule_partitions_tensors_and_respects_readiness():
     assert e.value.code == wk.KV_E_OVERLAP
 
 
+def test_materialize_schedule_in_a_layer_major_pool():
+    """The unit of readiness is a block's tile in one strip: an early piece touches only tiles of
+    blocks that were free before the move, whichever strip it lies in."""
+    import numpy as np
+    from synth import bitmap_from_ids
+    nb, b, layers, tile = 80, 30, 3, 256
+    strip = (nb - b) * tile
+    rs = np.random.default_rng(5)
+    live_bits = rs.random(nb) < 0.5
+    live = bitmap_from_ids(np.flatnonzero(live_bits), nb)
+    pool = wk.pool_desc(FAKE, nb, layers, tile, nb * tile + 512)
+    tensors = [(FAKE, 5 * tile + 9, 100), (FAKE, strip - 7 * tile, strip + 7 * tile), (FAKE, 0, 2 * strip),
+               (FAKE, 3 * tile, 2 * strip + 11), (FAKE, tile // 2, 2 * strip + 20 * tile + 3)]
+    for budget in (1, 9 * tile, 1 << 40):
+        pieces = wk.weights_materialize_schedule(pool, b, live, tensors, early_bytes=budget)
+        early_total = 0
+        for i, (_, nbytes, off) in enumerate(tensors):
+            mine = sorted((p for p in pieces if p[0] == i), key=lambda p: p[2])
+            pos = 0
+            for _, early, so, do, n in mine:
+                assert so == pos and do == off + so and n > 0
+                pos += n
+                assert do // strip == (do + n - 1) // strip, "a piece stays inside its strip"
+                first, last = (do % strip) // tile, ((do + n - 1) % strip) // tile
+                if early:
+                    assert not live_bits[b + first:b + last + 1].any()
+                    early_total += n
+                elif budget == 1 << 40:
+                    assert live_bits[b + first:b + last + 1].all(), "with no budget limit only live tiles wait"
+            assert pos == nbytes
+        assert early_total < budget + tile
+    with pytest.raises(wk.WarmKVError) as e:      # a tensor across two strips is not contiguous in memory
+        wk.weights_materialize_schedule(pool, b, live, [(FAKE, 2, strip - 1)])
+    assert e.value.code == wk.KV_E_TOOBIG
+
+
+def test_grow_in_a_layer_major_pool_matches_oracle(oracle):
+    import numpy as np
+    nb, layers, tile = 50, 4, 128
+    pool = wk.pool_desc(FAKE, nb, layers, tile, nb * tile + 256)
+    rs = np.random.default_rng(21)
+    for _ in range(400):
+        old = int(rs.integers(0, nb))
+        new = int(rs.integers(old, nb + 1))
+        strip = (nb - old) * tile
+        ext = []
+        for _ in range(int(rs.integers(0, 8))):
+            layer, within = int(rs.integers(0, layers)), int(rs.integers(0, strip))
+            ext.append((int(rs.integers(0, strip - within + 1)), layer * strip + within))
+        if rs.random() < 0.2:
+            ext.append((0, layers * strip))                    # an empty extent at the very end
+        n, ev, no = wk.kv_grow(pool, old, new, [(FAKE, b, o) for b, o in ext])
+        on, oev, ono = oracle.grow_strips(tile, layers, nb, nb * tile + 256, old, new, ext)
+        assert n == on and ev == oev.tolist() and no == ono.tolist(), (old, new, ext)
+    for ext, code in (([(2, (nb - 10) * tile - 1)], wk.KV_E_TOOBIG), ([(1, layers * (nb - 10) * tile)], wk.KV_E_TOOBIG)):
+        with pytest.raises(wk.WarmKVError) as e:
+            wk.kv_grow(pool, 10, 20, [(FAKE, b, o) for b, o in ext])
+        assert e.value.code == code
+        assert oracle.grow_strips(tile, layers, nb, nb * tile + 256, 10, 20, ext)[0] == oracle.E_TOOBIG
+
+
 def test_reserve_blocks_matches_eq4_fixtures():
     with open(os.path.join(ROOT, "tests", "golden", "eq4_reserve.json")) as f:
         cases = json.load(f)["cases"]
@@ -341,9 +402,10 @@ def test_front_first_stream_validates_like_the_plain_one():
         with pytest.raises(wk.WarmKVError) as e:
             wk.weights_materialize_front(pool, b, 8192, tensors)
         assert e.value.code == code
-    with pytest.raises(wk.WarmKVError) as e:      # layer-major pools: the region is L strips, there is no single front
-        wk.weights_materialize_front(wk.pool_desc(FAKE + (1 << 20), nb, 2, tile, nb * tile), b, 8192, [(FAKE, 16, 0)])
-    assert e.value.code == wk.KV_E_RANGE
+    with pytest.raises(wk.WarmKVError) as e:      # layer-major pools: a tensor must lie inside one strip
+        wk.weights_materialize_front(wk.pool_desc(FAKE + (1 << 20), nb, 2, tile, nb * tile), b, 8192,
+                                     [(FAKE, 32, (nb - b) * tile - 16)])
+    assert e.value.code == wk.KV_E_TOOBIG
 
 
 def test_host_code_under_sanitizers(tmp_path):

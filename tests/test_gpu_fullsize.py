@@ -326,26 +326,103 @@ class WeightedPool:
         self.cid = np.arange(cfg.num_blocks, dtype=np.int32)
         self.cid[self.p.dst] = self.p.src
         self.cid_d = gh.to_dev(self.cid)
+        # the same pool kept layer-major: 32 slabs of 1.25 GiB, strips of 512 MiB; strip l receives layer
+        # l's seven matrices and the l-th of 32 row slices of the embedding matrix (it does not fit a strip)
+        self.tile, self.stride = cfg.tile_bytes, cfg.num_blocks * cfg.tile_bytes
+        self.strip = (cfg.num_blocks - cfg.boundary) * cfg.tile_bytes
+        self.pool_lm = wk.pool_desc(self.pool_t, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, self.stride)
+        emb, emb_slice = len(self.sizes) - 1, self.sizes[-1] // cfg.num_layers
+        assert emb_slice * cfg.num_layers == self.sizes[-1] and emb_slice % 256 == 0
+        self.lm = []           # (host address, bytes, region offset, content id, byte offset in that content)
+        for l in range(cfg.num_layers):
+            at = l * self.strip
+            for i in range(7 * l, 7 * l + 7):
+                self.lm.append((self.host.data_ptr() + self.starts[i], self.sizes[i], at, i, 0))
+                at += self.sizes[i]
+            self.lm.append((self.host.data_ptr() + self.starts[emb] + l * emb_slice, emb_slice, at, emb, l * emb_slice))
+            at += emb_slice
+            assert at <= (l + 1) * self.strip
+        self.lm_tensors = [(a, n, o) for a, n, o, _, _ in self.lm]
         # full-buffer expectation: the oracle's block copy and weight copy on a host copy of the pool
-        if self.want_pool is not None:
-            self.fresh_pool()
-            content.copy_bytes(self.want_pool.ptr, self.pool_t.data_ptr(), cfg.pool_bytes)
+        self.expectation = None
+        self.mode = "full" if self.want_pool is not None else "lazy"
+        self.expect("block")
+        _say(f"[full] weights: comparison mode {self.mode}")
+
+    def expect(self, layout):
+        """Make the pinned host buffer hold what the oracle says the pool must be after the hand-over
+        in this layout (recomputed only when the layout changes)."""
+        if self.want_pool is None or self.expectation == layout:
+            return
+        cfg, oracle, bb = self.cfg, self.oracle, self.bb
+        self.fresh_pool(layout)
+        content.copy_bytes(self.want_pool.ptr, self.pool_t.data_ptr(), cfg.pool_bytes)
+        if layout == "block":
             _spot_check_host_copy(self.want_pool, cfg, self.table, [0, 1, cfg.boundary, cfg.num_blocks - 1, 7777])
             oracle.compact(self.want_pool.array, bb, self.p)
             views = [(self.host[st:st + sz].numpy(), off) for st, sz, off in zip(self.starts, self.sizes, self.offs)]
             assert oracle.materialize(self.want_pool.array, cfg.boundary * bb, views) == 0
-        self.mode = "full" if self.want_pool is not None else "lazy"
-        _say(f"[full] weights: comparison mode {self.mode}")
+        else:
+            for l, j in ((0, 0), (3, 7777), (cfg.num_layers - 1, cfg.num_blocks - 1)):   # slab l holds bytes [l*tile, (l+1)*tile) of each block
+                want = content.item_bytes_host(cfg.seed, j, 4096, self.table, byte_offset=l * self.tile)
+                at = l * self.stride + j * self.tile
+                assert np.array_equal(self.want_pool.array[at:at + 4096], want), (l, j)
+            oracle.compact_layer_major(self.want_pool.array, self.tile, cfg.num_layers, self.stride, self.p)
+            base = self.host.data_ptr()
+            views = [(self.host[a - base:a - base + n].numpy(), o) for a, n, o, _, _ in self.lm]
+            assert oracle.materialize_strips(self.want_pool.array, self.tile, cfg.num_layers, cfg.num_blocks,
+                                             cfg.boundary, self.stride, views) == 0
+        self.expectation = layout
 
-    def fresh_pool(self):
+    def fresh_pool(self, layout="block"):
         cfg = self.cfg
-        content.fill_device(self.pool_t.data_ptr(), cfg.num_blocks, self.bb, cfg.seed, table_ptr=self.table_d.data_ptr())
+        if layout == "block":
+            content.fill_device(self.pool_t.data_ptr(), cfg.num_blocks, self.bb, cfg.seed, table_ptr=self.table_d.data_ptr())
+        else:
+            for l in range(cfg.num_layers):
+                content.fill_device(self.pool_t.data_ptr() + l * self.stride, cfg.num_blocks, self.tile, cfg.seed,
+                                    table_ptr=self.table_d.data_ptr(), byte_offset=l * self.tile)
         self.tables_d = torch.from_numpy(self.w.tables).to(gh.dev())
         self.dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
         torch.cuda.synchronize()
 
+    def check_layer_major(self, what):
+        """As check(), for the layer-major pool: the whole buffer against the oracle (full mode), then
+        slab by slab against the oracle's plan, every strip's tensors, and every strip's tail."""
+        cfg, p, tile, stride, strip = self.cfg, self.p, self.tile, self.stride, self.strip
+        torch.cuda.synchronize()
+        st, src, dst, new_id, live_out = self.dp.results()
+        assert st.status == 0 and st.n_moves == p.n_moves and st.ticket == 0 and st.finished == 0
+        assert np.array_equal(src, p.src) and np.array_equal(dst, p.dst) and np.array_equal(new_id, p.new_id)
+        assert np.array_equal(self.tables_d.cpu().numpy(), self.want_tables), f"{what}: tables"
+        self.expect_ready("layer")
+        if self.want_pool is not None:
+            _device_equals_host(self.pool_t, self.want_pool, what)
+        nb, b = cfg.num_blocks, cfg.boundary
+        scratch = torch.empty(stride, dtype=torch.uint8, device=gh.dev())
+        used = [0] * cfg.num_layers
+        for a, n, o, cid, off in self.lm:
+            l = o // strip
+            used[l] = max(used[l], o - l * strip + n)
+            content.fill_device(self.stage.data_ptr(), 1, n, self.WSEED, cid0=cid, table_ptr=self.wtab_d.data_ptr(),
+                                byte_offset=off)
+            at = l * stride + b * tile + (o - l * strip)
+            assert torch.equal(self.pool_t[at:at + n], self.stage[:n]), f"{what}: tensor at region offset {o}"
+        for l in range(cfg.num_layers):
+            content.fill_device(scratch.data_ptr(), nb, tile, cfg.seed, cids_ptr=self.cid_d.data_ptr(),
+                                table_ptr=self.table_d.data_ptr(), byte_offset=l * tile)
+            slab = self.pool_t[l * stride:(l + 1) * stride]
+            assert torch.equal(slab[:b * tile], scratch[:b * tile]), f"{what}: slab {l} below the boundary"
+            tail = b * tile + used[l]
+            assert torch.equal(slab[tail:], scratch[tail:]), f"{what}: tail of strip {l}"
+        del scratch
+
+    def expect_ready(self, layout):
+        assert self.want_pool is None or self.expectation == layout, "call expect(layout) before running the path"
+
     def check(self, what):
         cfg, p, bb = self.cfg, self.p, self.bb
+        self.expect_ready("block")
         torch.cuda.synchronize()
         st, src, dst, new_id, live_out = self.dp.results()
         assert st.status == 0 and st.n_moves == p.n_moves and st.ticket == 0 and st.finished == 0
@@ -406,6 +483,7 @@ def test_full_size_reclaim_with_weights(weighted):
     block copy (the compaction event), then streams the 225 tensors."""
     wp = weighted
     cfg, w = wp.cfg, wp.w
+    wp.expect("block")
     wp.fresh_pool()
     wk.kv_plan_reclaim(wp.live_d, wp.dp.plan, wp.s_compute.cuda_stream)
     wk.kv_compact(wp.pool, wp.dp.plan, wp.s_compute.cuda_stream)
@@ -429,6 +507,7 @@ def test_full_size_switch_in_one_call(weighted, mode, order):
     wp = weighted
     cfg, w = wp.cfg, wp.w
     tensors = wp.tensors if order == "forward" else wp.tensors[::-1]
+    wp.expect("block")
     wp.fresh_pool()
     st = wk.kv_switch(wp.pool, wp.dp.plan, wp.live_d, wp.tables_d, w.tables.shape[0], w.tables.shape[1], tensors,
                       wp.s_compute.cuda_stream, wp.s_copy.cuda_stream, wp.done.cuda_event, live_host=w.live,
@@ -458,6 +537,7 @@ def test_full_size_front_first_weight_stream(weighted, mark, order):
     front_bytes = _front_marks(wp)[mark]
     tensors = wp.tensors if order == "forward" else wp.tensors[::-1]
     s, cs = wp.s_compute.cuda_stream, wp.s_copy.cuda_stream
+    wp.expect("block")
     wp.fresh_pool()
     head = wk.kv_movers_in_front(w.live, cfg.num_blocks, cfg.boundary, min(-(-front_bytes // bb), cfg.num_blocks))
     want_head = int(np.count_nonzero(wp.p.src < cfg.boundary + -(-front_bytes // bb)))
@@ -478,6 +558,7 @@ def test_full_size_block_pipelined_weight_stream(weighted):
     wp = weighted
     cfg, w = wp.cfg, wp.w
     s, cs = wp.s_compute.cuda_stream, wp.s_copy.cuda_stream
+    wp.expect("block")
     for early in (0, 1 << 40):
         wp.fresh_pool()
         wk.kv_plan_reclaim(wp.live_d, wp.dp.plan, s)
@@ -486,3 +567,37 @@ def test_full_size_block_pipelined_weight_stream(weighted):
         wk.weights_materialize_pipelined(wp.pool, cfg.boundary, w.live, wp.tensors[::-1], early, cs, wp.done.cuda_event)
         wk.kv_remap_tables(wp.tables_d, w.tables.shape[0], w.tables.shape[1], wp.dp.plan, s)
         wp.check(f"block-pipelined, early budget {early}")
+
+
+@pytest.mark.parametrize("path", ["gated", "switch_front", "switch_front_reverse", "switch_block", "front_3_strips_reverse"])
+def test_full_size_layer_major_weight_paths(weighted, path):
+    """The 8B-shaped pool kept layer-major (32 slabs of 1.25 GiB, strips of 512 MiB), with the same
+    15 GB of weights placed strip by strip, the table rewrite, and every overlapped weight path."""
+    wp = weighted
+    cfg, w = wp.cfg, wp.w
+    s, cs = wp.s_compute.cuda_stream, wp.s_copy.cuda_stream
+    tensors = wp.lm_tensors[::-1] if path.endswith("reverse") else wp.lm_tensors
+    wp.expect("layer")
+    wp.fresh_pool("layer")
+    if path == "gated":
+        wk.kv_plan_reclaim(wp.live_d, wp.dp.plan, s)
+        wk.kv_compact(wp.pool_lm, wp.dp.plan, s)
+        wp.done.record(wp.s_compute)
+        wk.weights_materialize(wp.pool_lm, cfg.boundary, tensors, cs, wp.done.cuda_event)
+        wk.kv_remap_tables(wp.tables_d, w.tables.shape[0], w.tables.shape[1], wp.dp.plan, s)
+    elif path.startswith("switch"):
+        st = wk.kv_switch(wp.pool_lm, wp.dp.plan, wp.live_d, wp.tables_d, w.tables.shape[0], w.tables.shape[1], tensors,
+                          s, cs, wp.done.cuda_event, live_host=w.live,
+                          front_done=wp.front.cuda_event if "front" in path else None)
+        assert st.status == 0 and st.n_moves == wp.p.n_moves
+    else:
+        front_bytes = 2 * wp.strip + 4096           # needs the first three strips
+        wk.kv_plan_reclaim(wp.live_d, wp.dp.plan, s)
+        wk.kv_compact_layers(wp.pool_lm, wp.dp.plan, 0, 3, s)
+        wp.front.record(wp.s_compute)
+        wk.kv_compact_layers(wp.pool_lm, wp.dp.plan, 3, 0xFFFFFFFF, s)
+        wp.done.record(wp.s_compute)
+        wk.kv_remap_tables(wp.tables_d, w.tables.shape[0], w.tables.shape[1], wp.dp.plan, s)
+        wk.weights_materialize_front(wp.pool_lm, cfg.boundary, front_bytes, tensors, cs, wp.front.cuda_event,
+                                     wp.done.cuda_event)
+    wp.check_layer_major(f"layer-major {path}")

@@ -624,6 +624,141 @@ def test_layer_major_reclaim_matches_oracle(oracle, name):
     assert e.value.code == wk.KV_E_RANGE
 
 
+def _strip_tensors(cfg, seed):
+    """Weight extents for a layer-major pool: several per strip, never across a strip end; one
+    starts a strip, one ends the last strip exactly, one is empty.  Returns (hosts, sizes, offs)."""
+    strip = (cfg.num_blocks - cfg.boundary) * cfg.tile_bytes
+    tile = cfg.tile_bytes
+    sizes, offs = [], []
+    for l in range(cfg.num_layers):
+        a = min(strip // 3, 5 * tile + 48) // 16 * 16
+        sizes += [a, min(strip - strip // 2, 3 * tile) // 16 * 16]
+        offs += [l * strip + (16 if l else 0), l * strip + strip // 2 // 16 * 16]
+    sizes += [0, min(strip // 4, 2 * tile + 16) // 16 * 16]
+    offs += [strip, (cfg.num_layers - 1) * strip + strip - min(strip // 4, 2 * tile + 16) // 16 * 16]
+    hosts = []
+    for i, sz in enumerate(sizes):
+        h = torch.empty(max(sz, 16), dtype=torch.uint8, pin_memory=True)
+        h.numpy()[:sz] = content.item_bytes_host(seed, i, -(-sz // 8) * 8, None)[:sz]
+        hosts.append(h)
+    return hosts, sizes, offs
+
+
+@pytest.mark.parametrize("name", ["lm_small", "lm_padded_slabs", "lm_16k_tile"])
+def test_layer_major_pipelined_weight_paths_match_oracle(oracle, name):
+    """Layer-major pools through every overlapped weight path: block copy by layer ranges with the
+    front-first stream (the region is ready strip by strip), the tile-granular schedule, and
+    kv_switch in all three modes.  Pool and tables against the oracle's layer-major steps."""
+    cfg, pad = LAYER_MAJOR[name]
+    w = make_workload(cfg)
+    pool0, stride = _layer_major_pool(cfg, pad)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    hosts, sizes, offs = _strip_tensors(cfg, 0x77)
+    want = pool0.copy()
+    oracle.compact_layer_major(want, cfg.tile_bytes, cfg.num_layers, stride, p)
+    assert oracle.materialize_strips(want, cfg.tile_bytes, cfg.num_layers, cfg.num_blocks, cfg.boundary, stride,
+                                     [(h.numpy()[:sz], o) for h, sz, o in zip(hosts, sizes, offs)]) == 0
+    want_tables = w.tables.copy()
+    assert oracle.remap(want_tables, p) == 0
+    strip = (cfg.num_blocks - cfg.boundary) * cfg.tile_bytes
+    L = cfg.num_layers
+    order = list(range(len(sizes)))[::-1]            # listed from the last strip back to the first
+    tensors = [(hosts[i], sizes[i], offs[i]) for i in order]
+    s_compute, s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+    done, front_done = torch.cuda.Event(), torch.cuda.Event()
+    done.record(s_compute)
+    front_done.record(s_compute)
+    live_dev = gh.to_dev(w.live)
+
+    def fresh():
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        return (pool_dev, wk.pool_desc(pool_dev, cfg.num_blocks, L, cfg.tile_bytes, stride),
+                torch.from_numpy(w.tables).to(gh.dev()), gh.DevicePlan(cfg.num_blocks, cfg.boundary))
+
+    def check(pool_dev, tables_dev, dp, what):
+        torch.cuda.synchronize()
+        st = _compare_plan(dp, p)
+        assert st.ticket == 0 and st.finished == 0 and st.bad_plan == 0
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), what
+        assert np.array_equal(pool_dev.cpu().numpy(), want), what
+
+    cs, ss = s_compute.cuda_stream, s_copy.cuda_stream
+    # explicit front-first: the first f strips behind the first event
+    for front_bytes in (0, 1, strip, strip + 16, (L - 1) * strip + strip // 2, L * strip + 99):
+        f = min(L, -(-front_bytes // strip))
+        pool_dev, pool, tables_dev, dp = fresh()
+        torch.cuda.synchronize()
+        wk.kv_plan_reclaim(live_dev, dp.plan, cs)
+        wk.kv_compact_layers(pool, dp.plan, 0, f, cs)
+        front_done.record(s_compute)
+        wk.kv_compact_layers(pool, dp.plan, f, 0xFFFFFFFF, cs)
+        done.record(s_compute)
+        wk.kv_remap_tables(tables_dev, *w.tables.shape, dp.plan, cs)
+        wk.weights_materialize_front(pool, cfg.boundary, front_bytes, tensors, ss, front_done.cuda_event, done.cuda_event)
+        check(pool_dev, tables_dev, dp, f"front {front_bytes} ({f} strips)")
+    # tile-granular schedule
+    for early in (0, 3 * cfg.tile_bytes, 1 << 40):
+        pool_dev, pool, tables_dev, dp = fresh()
+        torch.cuda.synchronize()
+        wk.kv_plan_reclaim(live_dev, dp.plan, cs)
+        wk.kv_compact(pool, dp.plan, cs)
+        done.record(s_compute)
+        wk.weights_materialize_pipelined(pool, cfg.boundary, w.live, tensors, early, ss, done.cuda_event)
+        wk.kv_remap_tables(tables_dev, *w.tables.shape, dp.plan, cs)
+        check(pool_dev, tables_dev, dp, f"pipelined early={early}")
+    # one call
+    for mode, early in (("gated", 0), ("block", 0), ("front", 0), ("front", strip + 1), ("front", 1 << 40)):
+        pool_dev, pool, tables_dev, dp = fresh()
+        torch.cuda.synchronize()
+        st = wk.kv_switch(pool, dp.plan, live_dev, tables_dev, *w.tables.shape, tensors, cs, ss, done.cuda_event,
+                          live_host=None if mode == "gated" else w.live, early_bytes=early,
+                          front_done=front_done.cuda_event if mode == "front" else None)
+        assert st.status == 0 and st.n_moves == p.n_moves
+        check(pool_dev, tables_dev, dp, f"kv_switch {mode} early={early}")
+
+
+@pytest.mark.parametrize("layer_major", [False, True])
+def test_block_copy_of_a_range_of_layers(oracle, layer_major):
+    """kv_compact_layers copies exactly the tiles of the chosen layers of every move, in both
+    layouts, and consecutive ranges add up to the whole block copy."""
+    cfg = CONFIGS[1].scaled(num_blocks=400, num_layers=5, num_seqs=30)
+    w = make_workload(cfg)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    tile, L, nb = cfg.tile_bytes, cfg.num_layers, cfg.num_blocks
+    if layer_major:
+        pool0, stride = _layer_major_pool(cfg, 512)
+    else:
+        pool0, stride = gh.host_pool(cfg, gh.content_table(cfg)), 0
+
+    def tiles(buf, layer):      # view [num_blocks, tile] of one layer's tiles
+        if layer_major:
+            return buf[layer * stride:layer * stride + nb * tile].reshape(nb, tile)
+        return buf.reshape(nb, L, tile)[:, layer, :]
+
+    dp = gh.DevicePlan(nb, cfg.boundary)
+    wk.kv_plan_reclaim(gh.to_dev(w.live), dp.plan)
+    for first, count in ((0, 1), (2, 2), (4, 7), (5, 1), (1, 0), (0, 0xFFFFFFFF)):
+        want = pool0.copy()
+        for l in range(first, min(L, first + count)):
+            tiles(want, l)[p.dst] = tiles(pool0, l)[p.src]      # the oracle's moves, these layers only
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        wk.kv_compact_layers(wk.pool_desc(pool_dev, nb, L, tile, stride), dp.plan, first, count)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want), (first, count)
+        st = dp.state()
+        assert st.ticket == 0 and st.finished == 0
+    want = pool0.copy()
+    if layer_major:
+        oracle.compact_layer_major(want, tile, L, stride, p)
+    else:
+        oracle.compact(want, cfg.block_bytes, p)
+    pool_dev = torch.from_numpy(pool0).to(gh.dev())
+    for first, count in ((0, 2), (2, 1), (3, 9)):
+        wk.kv_compact_layers(wk.pool_desc(pool_dev, nb, L, tile, stride), dp.plan, first, count)
+    torch.cuda.synchronize()
+    assert np.array_equal(pool_dev.cpu().numpy(), want)
+
+
 def test_two_reclaims_on_two_streams_do_not_interfere(oracle):
     """The library keeps no global state: two pools, two plans, two streams, interleaved calls."""
     cfgs = [CONFIGS[1].scaled(num_blocks=1024, num_layers=4, num_seqs=64),

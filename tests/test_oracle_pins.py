@@ -328,6 +328,53 @@ def test_grow_hand_cases_and_byte_brute_force(oracle):
         assert n == int(ev.sum())
 
 
+def test_grow_strips_hand_cases_and_byte_brute_force(oracle):
+    """Reverse switch in a layer-major pool: every strip loses its first (new - old) tiles.  Checked
+    against a per-byte ownership map of the whole pool (slab padding included)."""
+    tile, layers, nb = 16, 3, 12
+    stride = nb * tile + 32                                   # padded slabs
+    # old boundary 4 (strips of 8 tiles = 128 B), 2 tiles returned per strip: slab bytes [64, 96)
+    ext = [(16, 0), (1, 31), (1, 32), (96, 32), (0, 5), (40, 128 + 40), (8, 2 * 128 + 24), (128, 2 * 128)]
+    n, ev, no = oracle.grow_strips(tile, layers, nb, stride, 4, 6, ext)
+    assert n == 4 and ev.tolist() == [1, 1, 0, 0, 0, 0, 1, 1]
+    # survivors keep their place: strips shrink to 6 tiles = 96 B
+    assert no.tolist()[2:6] == [0, 0, 0, 96 + 8]
+    assert oracle.grow_strips(tile, layers, nb, stride, 4, 6, [(2, 127)])[0] == oracle.E_TOOBIG     # straddles two strips
+    assert oracle.grow_strips(tile, layers, nb, stride, 4, 6, [(1, 3 * 128)])[0] == oracle.E_TOOBIG
+    assert oracle.grow_strips(tile, layers, nb, stride, 6, 4, [])[0] == oracle.E_RANGE
+    # one layer, stride = pool: the block-major function on the same numbers
+    for old, new in ((0, 0), (3, 9), (5, 12)):
+        e1 = [(7, 3), (0, 0), (20, 40)] if old <= 8 else []
+        a = oracle.grow_strips(tile, 1, nb, nb * tile, old, new, e1)
+        b = oracle.grow(tile, nb, old, new, e1)
+        assert a[0] == b[0] and (a[0] < 0 or (a[1].tolist() == b[1].tolist() and a[2].tolist() == b[2].tolist()))
+    rs = np.random.default_rng(8)
+    for _ in range(300):
+        old = int(rs.integers(0, nb))
+        new = int(rs.integers(old, nb + 1))
+        old_strip, new_strip = (nb - old) * tile, (nb - new) * tile
+        ext = []
+        for _ in range(5):
+            layer = int(rs.integers(0, layers))
+            within = int(rs.integers(0, old_strip))
+            ext.append((int(rs.integers(0, old_strip - within + 1)), layer * old_strip + within))
+        n, ev, no = oracle.grow_strips(tile, layers, nb, stride, old, new, ext)
+        returned = np.zeros(layers * stride, dtype=bool)       # bytes that go back to the KV cache
+        for l in range(layers):
+            returned[l * stride + old * tile:l * stride + new * tile] = True
+
+        def absolute(boundary, strip_bytes, region_offset):     # where a region offset lies in the pool
+            l, w = divmod(region_offset, strip_bytes)
+            return l * stride + boundary * tile + w
+
+        for i, (b, o) in enumerate(ext):
+            lo = absolute(old, old_strip, o)
+            assert bool(ev[i]) == bool(returned[lo:lo + b].any())
+            if b and not ev[i]:
+                assert absolute(new, new_strip, int(no[i])) == lo   # same absolute place under the new boundary
+        assert n == int(ev.sum())
+
+
 def _check_vmm_selection(live, want, ids):
     """Properties that fix the selection uniquely: `want` distinct unused blocks, highest first, and
     no unused block left out is higher than one that was taken."""

@@ -328,6 +328,29 @@ typedef struct kv_switch_request {
  * waiting for it. */
 int kv_switch(const kv_switch_request* request, kv_plan_state* result);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  kv_plan_reclaim +
+ * kv_compact + kv_remap_tables on `stream`, with the plan's workspace (the
+ * move lists, the id map, the work counters) in a static device array inside
+ * the library instead of a caller's buffer; the call allocates and frees
+ * nothing, on the host or on the device.  Inputs and outputs are the caller's:
+ * pool, live_in, tables as for the three calls; live_out [device,
+ * uint64[ceil(NB/64)], must not overlap live_in] receives the bitmap after the
+ * move and state_out [device, one kv_plan_state] the plan's header as
+ * kv_plan_fetch would report it (status KV_E_NOSPACE: nothing was moved or
+ * rewritten and live_out is unspecified).
+ * Limits: pool->num_blocks <= KV_STATIC_MAX_BLOCKS, else KV_E_TOOBIG and nothing
+ * is enqueued.  The array (about 2 MiB) exists once per GPU the library is
+ * used on, for the life of the process; its address on the current device is
+ * looked up on the first call there.  Every call on a GPU uses that one array:
+ * two calls that overlap in time on one GPU (different streams with no
+ * ordering between them) race, so order them.  Each call rewrites all of
+ * the array it reads, so a smaller request after a larger one is fine. */
+#define KV_STATIC_MAX_BLOCKS 262144u
+int kv_reclaim_static(const kv_pool_desc* pool, uint32_t boundary, const uint64_t* live_in,
+                      uint64_t* live_out, int32_t* tables, uint32_t num_seqs,
+                      uint32_t max_blocks_per_seq, kv_plan_state* state_out, void* stream);
+
 /* Reserved KV space of a draining instance, Sec. 3.3 Eq. 4, in blocks:
  * R = max(C*Q/B, T + C/B), fractional blocks rounded up, capped at C.
  * C = capacity_blocks (<= 2^32 - 1), T = used_blocks, Q = running requests,

@@ -35,13 +35,13 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
            "weights_materialize_pipelined", "kv_compact_moves", "kv_compact_layers", "kv_movers_in_front", "weights_materialize_front",
-           "kv_switch", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
+           "kv_switch", "kv_reclaim_static", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_reclaim_load", "kv_vmm_lent", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
            "ws_place_replicas", "warmkv_version", "warmkv_build_id")
 
 
 __all__ = [*EXPORTS, "KV_OK", "KV_E_NULL", "KV_E_RANGE", "KV_E_ALIGN", "KV_E_TOOBIG", "KV_E_OVERLAP", "KV_E_HIP",
-           "KV_E_NOSPACE", "KV_E_BADPLAN", "KV_E_NOMEM", "WarmKVError", "StaleLibraryError", "pool_desc", "make_model"]
+           "KV_E_NOSPACE", "KV_E_BADPLAN", "KV_E_NOMEM", "KV_STATIC_MAX_BLOCKS", "WarmKVError", "StaleLibraryError", "pool_desc", "make_model"]
 
 
 class WarmKVError(RuntimeError):
@@ -175,6 +175,9 @@ def load():
                                             c_void_p, c_void_p, c_void_p]
     L.kv_switch.restype = c_int
     L.kv_switch.argtypes = [POINTER(kv_switch_request), POINTER(kv_plan_state)]
+    L.kv_reclaim_static.restype = c_int
+    L.kv_reclaim_static.argtypes = [POINTER(kv_pool_desc), c_uint32, c_void_p, c_void_p, c_void_p, c_uint32, c_uint32,
+                                    c_void_p, c_void_p]
     L.kv_reserve_blocks.restype = c_int64
     L.kv_reserve_blocks.argtypes = [c_uint64, c_uint64, c_uint32, c_uint32]
     L.kv_grow.restype = c_int64
@@ -342,6 +345,18 @@ def kv_switch(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int,
     st = kv_plan_state()
     _check("kv_switch", load().kv_switch(byref(rq), byref(st)))
     return st
+
+
+KV_STATIC_MAX_BLOCKS = 262144
+
+
+def kv_reclaim_static(pool: kv_pool_desc, boundary: int, live_in, live_out, tables, num_seqs: int,
+                      max_blocks_per_seq: int, state_out, stream=0) -> None:
+    """Plan, block copy and table rewrite with the plan's workspace inside the library (no allocation).
+    live_out and state_out are device buffers of the caller's."""
+    _check("kv_reclaim_static", load().kv_reclaim_static(byref(pool), boundary, _ptr(live_in), _ptr(live_out),
+                                                          _ptr(tables), num_seqs, max_blocks_per_seq, _ptr(state_out),
+                                                          _ptr(stream)))
 
 
 def kv_reserve_blocks(capacity_blocks: int, used_blocks: int, running: int, max_batch: int) -> int:

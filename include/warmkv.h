@@ -342,7 +342,8 @@ int kv_switch(const kv_switch_request* request, kv_plan_state* result);
  * Limits: pool->num_blocks <= KV_STATIC_MAX_BLOCKS, else KV_E_TOOBIG and nothing
  * is enqueued.  The array (about 2 MiB) exists once per GPU the library is
  * used on, for the life of the process; its address on the current device is
- * looked up on the first call there.  Every call on a GPU uses that one array:
+ * looked up on the first call there (make that call outside stream capture;
+ * later calls may be captured).  Every call on a GPU uses that one array:
  * two calls that overlap in time on one GPU (different streams with no
  * ordering between them) race, so order them.  Each call rewrites all of
  * the array it reads, so a smaller request after a larger one is fine. */

@@ -82,6 +82,47 @@ def test_static_reclaim_matches_the_three_calls_twice_in_a_row(oracle):
     assert np.array_equal(pool_d.cpu().numpy(), pool0) and np.array_equal(tables_d.cpu().numpy(), w.tables)
 
 
+def test_static_reclaim_replays_from_a_hip_graph(oracle):
+    """The callers this entry point is for: captured once (after one eager call, which also looks up
+    the workspace's address on this device), replayed with eager work and synchronisation between
+    replays; every replay must give the oracle's result."""
+    cfg = CONFIGS[1].scaled(num_blocks=1200, num_layers=3, num_seqs=64)
+    w = make_workload(cfg)
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want_pool, want_tables = pool0.copy(), w.tables.copy()
+    oracle.compact(want_pool, cfg.block_bytes, p)
+    assert oracle.remap(want_tables, p) == 0
+    pool0_dev = torch.from_numpy(pool0).to(gh.dev())
+    pool_dev = pool0_dev.clone()
+    tables0_dev = torch.from_numpy(w.tables).to(gh.dev())
+    tables_dev = tables0_dev.clone()
+    live_in = gh.to_dev(w.live)
+    live_out = torch.zeros(((cfg.num_blocks + 63) // 64) * 8, dtype=torch.uint8, device=gh.dev())
+    state = torch.zeros(32, dtype=torch.uint8, device=gh.dev())
+    desc = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+    args = (desc, cfg.boundary, live_in, live_out, tables_dev, w.tables.shape[0], w.tables.shape[1], state)
+    side = torch.cuda.Stream()
+    wk.kv_reclaim_static(*args, side.cuda_stream)          # eager first call, outside any capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        wk.kv_reclaim_static(*args, torch.cuda.current_stream().cuda_stream)
+    for replay in range(3):
+        pool_dev.copy_(pool0_dev)                            # eager work between replays
+        tables_dev.copy_(tables0_dev)
+        live_out.fill_(0xEE)
+        state.fill_(0xEE)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        st = wk.binding.kv_plan_state.from_buffer_copy(state.cpu().numpy().tobytes())
+        assert (st.status, st.n_moves, st.ticket, st.finished, st.n_bad_entries) == (0, p.n_moves, 0, 0, 0)
+        assert np.array_equal(gh.from_dev(live_out, np.uint64), p.live_out), f"replay {replay}"
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), f"replay {replay}"
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), f"replay {replay}"
+
+
 def test_static_reclaim_refuses_what_does_not_fit():
     fake = 0x7F0000000000
     too_big = wk.pool_desc(fake, wk.KV_STATIC_MAX_BLOCKS + 1, 1, 4096)

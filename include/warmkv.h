@@ -174,6 +174,17 @@ int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
 int kv_remap_tables(int32_t* tables, uint32_t num_seqs, uint32_t max_blocks_per_seq,
                     const kv_plan* plan, void* stream);
 
+/* The reclaim step as one call: kv_plan_reclaim, kv_compact and kv_remap_tables
+ * on `stream`, with the same arguments, rules and results (all of the plan's
+ * arrays and its header are written as the three calls write them).  A small
+ * pool - at most 32 768 blocks, at most 16 384 table entries, at most 128 MiB
+ * of blocks that could move - takes a single kernel launch, in which every
+ * workgroup ranks the bitmap for itself so that none waits for another; on a
+ * pool of a thousand blocks the three launches and the gaps between them cost
+ * more than the work.  Larger pools take the three launches. */
+int kv_reclaim(const kv_pool_desc* pool, const kv_plan* plan, const uint64_t* live_in,
+               int32_t* tables, uint32_t num_seqs, uint32_t max_blocks_per_seq, void* stream);
+
 /* Synchronise `stream` and copy the plan's header to `out` [host];
  * out->status is KV_E_BADPLAN if the planner said KV_OK and kv_compact has
  * since skipped a move (state.bad_plan). */

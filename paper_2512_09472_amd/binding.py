@@ -33,7 +33,7 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
           KV_E_NOSPACE: "KV_E_NOSPACE", KV_E_BADPLAN: "KV_E_BADPLAN", KV_E_NOMEM: "KV_E_NOMEM"}
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
-           "kv_remap_tables", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
+           "kv_remap_tables", "kv_reclaim", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
            "weights_materialize_pipelined", "kv_compact_moves", "kv_compact_layers", "kv_movers_in_front", "weights_materialize_front",
            "kv_switch", "kv_reclaim_static", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_reclaim_load", "kv_vmm_lent", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
@@ -154,6 +154,8 @@ def load():
     L.kv_compact_launch.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), POINTER(kv_compact_tuning), c_void_p]
     L.kv_remap_tables.restype = c_int
     L.kv_remap_tables.argtypes = [c_void_p, c_uint32, c_uint32, POINTER(kv_plan), c_void_p]
+    L.kv_reclaim.restype = c_int
+    L.kv_reclaim.argtypes = [POINTER(kv_pool_desc), POINTER(kv_plan), c_void_p, c_void_p, c_uint32, c_uint32, c_void_p]
     L.kv_plan_fetch.restype = c_int
     L.kv_plan_fetch.argtypes = [POINTER(kv_plan), c_void_p, POINTER(kv_plan_state)]
     L.weights_materialize.restype = c_int
@@ -258,6 +260,13 @@ def kv_compact_launch(pool: kv_pool_desc, plan: kv_plan, stream=0, *, workgroups
 def kv_remap_tables(tables, num_seqs: int, max_blocks_per_seq: int, plan: kv_plan, stream=0) -> None:
     _check("kv_remap_tables", load().kv_remap_tables(_ptr(tables), num_seqs, max_blocks_per_seq, byref(plan),
                                                       _ptr(stream)))
+
+
+def kv_reclaim(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int, max_blocks_per_seq: int,
+               stream=0) -> None:
+    """Plan, block copy and table rewrite as one call (one kernel launch on small pools)."""
+    _check("kv_reclaim", load().kv_reclaim(byref(pool), byref(plan), _ptr(live_in), _ptr(tables), num_seqs,
+                                            max_blocks_per_seq, _ptr(stream)))
 
 
 def kv_plan_fetch(plan: kv_plan, stream=0) -> kv_plan_state:

@@ -9,6 +9,7 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 import gpu_harness as gh                      # noqa: E402
+import pins                                   # noqa: E402
 import paper_2512_09472_amd as wk             # noqa: E402
 from synth import CONFIGS, bitmap_from_ids, content, make_workload   # noqa: E402
 from synth.rng import SplitMix64              # noqa: E402
@@ -91,6 +92,123 @@ def test_reclaim_matches_oracle(oracle, name):
             bad = np.flatnonzero(got.reshape(cfg.num_blocks, -1) != want_pool.reshape(cfg.num_blocks, -1))[:5]
             pytest.fail(f"pool differs, first flat positions {bad}")
         del pool_dev
+
+
+ONE_CALL = {
+    # one kernel launch: at most 32 768 blocks, 16 384 table entries, 128 MiB that could move
+    "tiny_cfg1": (CONFIGS[0], 0, True),
+    "one_word": (CONFIGS[0].scaled(num_blocks=50, boundary=23, num_seqs=5, len_hi=160), 0, True),
+    "ragged_tile_3_layers": (CONFIGS[1].scaled(num_blocks=1000, num_layers=3, kv_heads=3, head_dim=40, num_seqs=30, len_hi=4096), 0, True),
+    "odd_boundary": (CONFIGS[3].scaled(num_blocks=777, num_layers=2, num_seqs=40, len_hi=4096), 0, True),
+    "tiny_tiles_many_blocks": (CONFIGS[4].scaled(num_blocks=32768, num_layers=2, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=1000), 0, True),
+    "frag": (CONFIGS[4].scaled(num_blocks=256, num_layers=1, num_seqs=64, len_hi=512), 0, True),
+    "layer_major": (CONFIGS[1].scaled(num_blocks=640, num_layers=3, num_seqs=40, len_hi=4096), 512, True),
+    "layer_major_small_tile": (CONFIGS[4].scaled(num_blocks=2048, num_layers=6, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=512), 0, True),
+    # these take the three launches: too many blocks, too many table entries, too many bytes
+    "too_many_blocks": (CONFIGS[4].scaled(num_blocks=32769, num_layers=1, block_size=1, kv_heads=1, head_dim=8, len_hi=16, num_seqs=1000), 0, False),
+    "wide_tables": (CONFIGS[1].scaled(num_blocks=640, num_layers=1, num_seqs=40), 0, False),
+    "big_blocks": (CONFIGS[1].scaled(num_blocks=640, num_layers=9, num_seqs=40, len_hi=4096), 0, False),
+}
+
+
+@pytest.mark.parametrize("name", list(ONE_CALL))
+def test_reclaim_in_one_call_matches_oracle(oracle, name):
+    """kv_reclaim: same plan arrays, header, pool bytes and tables as the oracle's steps, whichever
+    way it runs (one launch on small pools, the three launches otherwise), twice in one workspace."""
+    cfg, pad, one_launch = ONE_CALL[name]
+    w = make_workload(cfg)
+    n_entries = w.tables.size
+    small = (cfg.num_blocks <= 32768 and n_entries <= 16384
+             and min(cfg.boundary, cfg.num_blocks - cfg.boundary) * cfg.block_bytes <= 128 << 20)
+    assert small == one_launch, "the case must take the path it is named for"
+    layer_major = "layer_major" in name
+    if layer_major:
+        pool0, stride = _layer_major_pool(cfg, pad)
+    else:
+        pool0, stride = gh.host_pool(cfg, gh.content_table(cfg)), 0
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    assert p.status == 0 and p.n_moves > 0
+    want_pool, want_tables = pool0.copy(), w.tables.copy()
+    if layer_major:
+        oracle.compact_layer_major(want_pool, cfg.tile_bytes, cfg.num_layers, stride, p)
+    else:
+        oracle.compact(want_pool, cfg.block_bytes, p)
+    assert oracle.remap(want_tables, p) == 0
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    live_dev = gh.to_dev(w.live)
+    stream = torch.cuda.Stream()
+    for rep in range(2):
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        tables_dev = torch.from_numpy(w.tables).to(gh.dev())
+        dp.ws.fill_(0x5A if rep else 0xA5)
+        torch.cuda.synchronize()
+        wk.kv_reclaim(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, stride), dp.plan, live_dev,
+                      tables_dev, *w.tables.shape, stream.cuda_stream)
+        torch.cuda.synchronize()
+        st = _compare_plan(dp, p)
+        assert (st.n_free_below, st.n_bad_entries, st.ticket, st.finished, st.bad_plan) == \
+               (int((~pins.bools_from_words(w.live, cfg.num_blocks)[:cfg.boundary]).sum()), 0, 0, 0, 0)
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), "tables"
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), "pool"
+
+
+def test_reclaim_in_one_call_special_cases(oracle):
+    """Degenerate pools, an infeasible request, bad table entries and a junk-padded bitmap through
+    the single-launch path."""
+    tile = 4096
+    for nb, b, ids in ((0, 0, []), (1, 1, []), (70, 0, []), (70, 70, list(range(70))), (70, 35, list(range(35))),
+                       (70, 35, []), (129, 64, [0, 63]), (64, 0, []), (130, 65, [3, 64, 70, 129])):
+        live = bitmap_from_ids(np.array(ids, dtype=np.int64), nb)
+        if live.size:
+            live[-1] |= np.uint64(0xFFFFFFFFFFFFFFFF) << np.uint64(nb % 64) if nb % 64 else np.uint64(0)   # junk past NB
+        p = oracle.plan(live, nb, b)
+        assert p.status == 0
+        pool0 = np.random.default_rng(nb + b).integers(0, 256, max(nb, 1) * tile, dtype=np.uint8)
+        want_pool = pool0.copy()
+        if nb:
+            oracle.compact(want_pool[:nb * tile], tile, p)
+        tables = np.array([ids[:4] + [-1] * (4 - len(ids[:4]))], dtype=np.int32)
+        want_tables = tables.copy()
+        assert oracle.remap(want_tables, p) == 0
+        pool_dev, tables_dev = torch.from_numpy(pool0).to(gh.dev()), torch.from_numpy(tables).to(gh.dev())
+        dp = gh.DevicePlan(nb, b)
+        wk.kv_reclaim(wk.pool_desc(pool_dev, nb, 1, tile), dp.plan, gh.to_dev(live) if live.size else None, tables_dev, 1, 4)
+        torch.cuda.synchronize()
+        st = _compare_plan(dp, p) if nb else dp.state()
+        assert st.status == 0 and st.n_moves == p.n_moves and st.n_bad_entries == 0, (nb, b)
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), (nb, b)
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), (nb, b)
+    # infeasible: one more live block than fits below the boundary; nothing may change
+    cfg = CONFIGS[0].scaled(num_blocks=300, boundary=100, num_seqs=16, live_budget_override=101)
+    w = make_workload(cfg)
+    assert oracle.plan(w.live, cfg.num_blocks, cfg.boundary).status == oracle.E_NOSPACE
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    pool_dev, tables_dev = torch.from_numpy(pool0).to(gh.dev()), torch.from_numpy(w.tables).to(gh.dev())
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    wk.kv_reclaim(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes), dp.plan, gh.to_dev(w.live),
+                  tables_dev, *w.tables.shape)
+    torch.cuda.synchronize()
+    st = dp.state()
+    assert st.status == wk.KV_E_NOSPACE and st.n_moves == 0 and st.ticket == 0 and st.finished == 0
+    assert np.array_equal(pool_dev.cpu().numpy(), pool0) and np.array_equal(tables_dev.cpu().numpy(), w.tables)
+    # bad table entries: left alone and counted, like the oracle
+    cfg = CONFIGS[0].scaled(num_blocks=256, boundary=128, num_seqs=16)
+    w = make_workload(cfg)
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    free_ids = np.flatnonzero(~pins.bools_from_words(w.live, cfg.num_blocks))
+    tables = w.tables.copy()
+    tables[0, :4] = [int(free_ids[0]), int(free_ids[-1]), cfg.num_blocks, 2**31 - 1]
+    tables[3, 7] = int(p.dst[0])                      # a free id that becomes a destination: still a bad entry
+    want_tables = tables.copy()
+    n_bad = oracle.remap(want_tables, p)
+    assert n_bad == 5
+    pool_dev, tables_dev = torch.from_numpy(gh.host_pool(cfg, gh.content_table(cfg))).to(gh.dev()), torch.from_numpy(tables).to(gh.dev())
+    dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+    wk.kv_reclaim(wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes), dp.plan, gh.to_dev(w.live),
+                  tables_dev, *tables.shape)
+    torch.cuda.synchronize()
+    assert dp.state().n_bad_entries == n_bad
+    assert np.array_equal(tables_dev.cpu().numpy(), want_tables)
 
 
 def test_device_fill_matches_host_generator():

@@ -39,11 +39,19 @@ struct SmallArgs {
   uint32_t n_entries;
 };
 
-// len bytes (multiple of 16), all 256 lanes: eight 128-bit loads in flight per lane, then a tail.
+// len bytes (multiple of 16), all 256 lanes: sixteen 128-bit loads in flight per lane (a whole
+// 64 KiB chunk in one round trip), then eight, then a tail.
 __device__ __forceinline__ void copy_span(const u32x4* __restrict__ sp, u32x4* __restrict__ dp, uint32_t len,
                                           uint32_t tid) {
   const uint32_t n = len / kVec;
   uint32_t i = tid;
+  for (; i + 15u * kThreads < n; i += 16u * kThreads) {
+    u32x4 v[16];
+#pragma unroll
+    for (int j = 0; j < 16; ++j) v[j] = __builtin_nontemporal_load(sp + i + j * kThreads);
+#pragma unroll
+    for (int j = 0; j < 16; ++j) __builtin_nontemporal_store(v[j], dp + i + j * kThreads);
+  }
   for (; i + 7u * kThreads < n; i += 8u * kThreads) {
     u32x4 v[8];
 #pragma unroll
@@ -171,17 +179,40 @@ __global__ __launch_bounds__(kThreads) void reclaim_small_kernel(SmallArgs a) {
 
   // ---- workgroup 0: table rewrite, count of the entries left alone, and the plan's header
   uint32_t bad = 0;
-  for (uint32_t i = tid; i < a.n_entries; i += kThreads) {
-    const int32_t e = a.tables[i];
-    if (e < 0) continue;
-    if ((uint32_t)e >= nb) { ++bad; continue; }
+  auto remap_one = [&](int32_t e) -> int32_t {
+    if (e < 0) return e;
+    if ((uint32_t)e >= nb) { ++bad; return e; }
     const uint32_t w = (uint32_t)e >> 6, bit = (uint32_t)e & 63u;
     const uint64_t live = s_live[w];
-    if (!((live >> bit) & 1ull)) { ++bad; continue; }
-    if ((uint32_t)e < b) continue;  // stays where it is
+    if (!((live >> bit) & 1ull)) { ++bad; return e; }
+    if ((uint32_t)e < b) return e;  // stays where it is
     const uint64_t movers = live & ~low_mask(w * 64u, b);
     const uint32_t k = (uint32_t)(s_rank[w] >> 32) + (uint32_t)__popcll(movers & ((1ull << bit) - 1ull));
-    a.tables[i] = (int32_t)kth_free(k);
+    return (int32_t)kth_free(k);
+  };
+  // Four 128-bit loads per lane are in flight before the first entry is looked at: one workgroup
+  // has the whole table, so the loads' latency must not add up entry by entry.
+  const uint32_t n_vec = a.n_entries / 4u;
+  i32x4* tv = (i32x4*)a.tables;
+  for (uint32_t i0 = tid; i0 < n_vec; i0 += 4u * kThreads) {
+    i32x4 e[4];
+#pragma unroll
+    for (uint32_t j = 0; j < 4u; ++j)
+      if (i0 + j * kThreads < n_vec) e[j] = tv[i0 + j * kThreads];
+#pragma unroll
+    for (uint32_t j = 0; j < 4u; ++j) {
+      if (i0 + j * kThreads >= n_vec) break;
+      i32x4 r;
+      r.x = remap_one(e[j].x);
+      r.y = remap_one(e[j].y);
+      r.z = remap_one(e[j].z);
+      r.w = remap_one(e[j].w);
+      if (r.x != e[j].x || r.y != e[j].y || r.z != e[j].z || r.w != e[j].w) tv[i0 + j * kThreads] = r;
+    }
+  }
+  for (uint32_t i = n_vec * 4u + tid; i < a.n_entries; i += kThreads) {  // up to three tail entries
+    const int32_t e = a.tables[i], r = remap_one(e);
+    if (r != e) a.tables[i] = r;
   }
 #pragma unroll
   for (int off = kWave / 2; off > 0; off >>= 1) bad += __shfl_xor(bad, off, kWave);

@@ -206,8 +206,8 @@ def cpu_baseline(cfg, w, sample_moves: int, weights=None):
         assert rc == 0 and np.array_equal(region[offs[-1]:offs[-1] + 4096], views[-1][0][:4096])
         total_w = sum(sizes)
         out["materialize"] = {"ms": round(t_mat * 1e3, 2), "GBps": round(total_w / t_mat / 1e9, 3),
-                              "sample": f"oracle weight copy of all {len(sizes)} tensors ({total_w} B), host memory "
-                                        "to host memory, one thread"}
+                              "sample": f"oracle weight copy of all {len(sizes)} tensors ({total_w} B), pinned host "
+                                        "memory (the weights as parked for the GPU) to pageable host memory, one thread"}
     return out
 
 

@@ -1279,3 +1279,25 @@ def test_randomized_reclaims_against_the_oracle(oracle):
         assert st.n_bad_entries == bad and st.ticket == 0 and st.finished == 0
         assert np.array_equal(tables_dev.cpu().numpy(), want_tables), case
         assert np.array_equal(pool_dev.cpu().numpy(), want_pool), case
+        # the same pool through kv_reclaim (a single launch at these sizes) and through kv_reclaim_static
+        for entry in ("kv_reclaim", "kv_reclaim_static"):
+            pool_dev.copy_(torch.from_numpy(pool0))
+            tables_dev.copy_(torch.from_numpy(tables))
+            if entry == "kv_reclaim":
+                dp.ws.fill_(0x3C)
+                torch.cuda.synchronize()
+                wk.kv_reclaim(pool, dp.plan, live_dev, tables_dev, rows, cols)
+                torch.cuda.synchronize()
+                st = _compare_plan(dp, p)
+            else:
+                live_out = torch.full((max(1, live.size) * 8,), 0x77, dtype=torch.uint8, device=gh.dev())
+                state = torch.zeros(32, dtype=torch.uint8, device=gh.dev())
+                wk.kv_reclaim_static(pool, b, live_dev, live_out, tables_dev, rows, cols, state)
+                torch.cuda.synchronize()
+                st = wk.binding.kv_plan_state.from_buffer_copy(state.cpu().numpy().tobytes())
+                assert st.status == p.status and st.n_moves == p.n_moves
+                if p.status == 0:
+                    assert np.array_equal(gh.from_dev(live_out, np.uint64)[:live.size], p.live_out), (case, entry)
+            assert st.n_bad_entries == (bad if p.status == 0 else 0) and st.ticket == 0 and st.finished == 0, (case, entry)
+            assert np.array_equal(tables_dev.cpu().numpy(), want_tables), (case, entry)
+            assert np.array_equal(pool_dev.cpu().numpy(), want_pool), (case, entry)

@@ -295,15 +295,25 @@ def main():
     pool_t = torch.empty(cfg.pool_bytes, dtype=torch.uint8, device=dev)
     table = content.normal_bf16_table(1.0) if cfg.content == "bf16_normal" else None
     table_d = torch.from_numpy(table.view(np.int16)).to(dev) if table is not None else None
-    content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed,
-                        table_ptr=table_d.data_ptr() if table_d is not None else 0)
+    layer_stride = cfg.num_blocks * cfg.tile_bytes if args.layout == "layer" else 0
+
+    def fill_pool():
+        """Block i holds content id i; in a layer-major pool slab l holds bytes [l*tile, (l+1)*tile) of each."""
+        tp = table_d.data_ptr() if table_d is not None else 0
+        if not layer_stride:
+            content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed, table_ptr=tp)
+        else:
+            for l in range(cfg.num_layers):
+                content.fill_device(pool_t.data_ptr() + l * layer_stride, cfg.num_blocks, cfg.tile_bytes, cfg.seed,
+                                    table_ptr=tp, byte_offset=l * cfg.tile_bytes)
+
+    fill_pool()
     live_d = torch.from_numpy(w.live.view(np.int64)).to(dev)
     tables0_d = torch.from_numpy(w.tables).to(dev)
     tables_d = tables0_d.clone()
     ws_bytes = wk.kv_plan_workspace_bytes(cfg.num_blocks, cfg.boundary)
     ws = torch.zeros(ws_bytes, dtype=torch.uint8, device=dev)
     plan = wk.kv_plan_bind(ws, ws_bytes, cfg.num_blocks, cfg.boundary)
-    layer_stride = cfg.num_blocks * cfg.tile_bytes if args.layout == "layer" else 0
     pool = wk.pool_desc(pool_t, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes, layer_stride)
     stream = torch.cuda.Stream()
     s = stream.cuda_stream
@@ -438,8 +448,7 @@ def main():
             ts.append(e0.elapsed_time(e1))
         out["comparators"] = {"contiguous_hipMemcpyDtoD_GBps_rw": round(2 * half / min(ts[1:]) / 1e6, 1),
                               "note": f"one contiguous copy of {half / 2**30:.2f} GiB, top of the pool to its bottom"}
-        content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed,
-                            table_ptr=table_d.data_ptr() if table_d is not None else 0)
+        fill_pool()
         torch.cuda.synchronize()
 
     tptr = table_d.data_ptr() if table_d is not None else 0
@@ -467,7 +476,7 @@ def main():
                      f"boundary {cfg.boundary})"] = (dataclasses.replace(cfg, live_budget_override=int(
                          round(cfg.occupancy * cfg.num_blocks))), cfg.boundary)
         variants[f"boundary = live count - 1 ({w.live_count - 1})"] = (cfg, w.live_count - 1)
-        content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed, table_ptr=tptr)
+        fill_pool()
         torch.cuda.synchronize()
         out["must_fail"] = {}
         for name, (vcfg, vb) in variants.items():
@@ -491,7 +500,7 @@ def main():
 
     # ---- weight materialisation leg (third configuration: same pool plus weights)
     weights_for_oracle = host_weights = None
-    if not args.no_materialize and cfg.index in (1, 2) and args.layout == "block" and not args.kv_heads:
+    if not args.no_materialize and cfg.index in (1, 2) and not args.kv_heads:
         shapes = weight_shapes_8b()
         sizes = [2 * a * b for _, (a, b) in shapes]
         offs = dense_offsets(sizes)
@@ -506,11 +515,31 @@ def main():
             pos += sz
         torch.cuda.synchronize()
         del stage
-        tensors, starts, pos = [], [], 0
-        for sz, off in zip(sizes, offs):
-            tensors.append((host.data_ptr() + pos, sz, off))
-            starts.append(pos)
-            pos += sz
+        starts = np.concatenate([[0], np.cumsum(sizes)[:-1]]).tolist()
+        region0 = cfg.boundary * bb
+        tile, strip = cfg.tile_bytes, (cfg.num_blocks - cfg.boundary) * cfg.tile_bytes
+        # pieces: (offset in the pinned buffer, bytes, region offset, content id, byte offset in that content)
+        if not layer_stride:
+            pieces = [(st_, sz, off, i, 0) for i, (st_, sz, off) in enumerate(zip(starts, sizes, offs))]
+        else:
+            # strip l takes layer l's seven matrices and the l-th of L row slices of the embedding matrix
+            # (1.05 GB: it fits no 512 MiB strip whole)
+            emb, emb_slice = len(sizes) - 1, sizes[-1] // cfg.num_layers
+            pieces = []
+            for l in range(cfg.num_layers):
+                at = l * strip
+                for i in range(7 * l, 7 * l + 7):
+                    pieces.append((starts[i], sizes[i], at, i, 0))
+                    at += sizes[i]
+                pieces.append((starts[emb] + l * emb_slice, emb_slice, at, emb, l * emb_slice))
+                assert at + emb_slice <= (l + 1) * strip
+        tensors = [(host.data_ptr() + st_, sz, off) for st_, sz, off, _, _ in pieces]
+
+        def device_offset(region_offset):
+            if not layer_stride:
+                return region0 + region_offset
+            l, within = divmod(region_offset, strip)
+            return l * layer_stride + cfg.boundary * tile + within
         weights_for_oracle = (host, starts, sizes, offs)
         copy_stream = torch.cuda.Stream()
         cs = copy_stream.cuda_stream
@@ -561,7 +590,6 @@ def main():
 
         # the link's measured ceiling: one plain pinned-to-device copy of 4 GiB into the same region
         n_plain = min(4 << 30, total)
-        region0 = cfg.boundary * bb
 
         def plain_copy():
             with torch.cuda.stream(copy_stream):
@@ -589,17 +617,33 @@ def main():
         stage = torch.empty(max(sizes), dtype=torch.uint8, device=dev)
 
         def verified(fn):
-            content.fill_device(pool_t.data_ptr(), cfg.num_blocks, bb, cfg.seed, table_ptr=tptr)
+            fill_pool()
             torch.cuda.synchronize()
             fn()
             torch.cuda.synchronize()
             ok = np.array_equal(tables_d.cpu().numpy(), tables_x)
-            ok = ok and pool_blocks_equal(cid_x, 0, cfg.boundary)                  # moved and kept KV
-            for i, (sz, off) in enumerate(zip(sizes, offs)):                       # every tensor
-                content.fill_device(stage.data_ptr(), 1, sz, 0x5EED0002, cid0=i, table_ptr=wtab.data_ptr())
-                ok = ok and torch.equal(pool_t[region0 + off:region0 + off + sz], stage[:sz])
-            end = region0 + offs[-1] + sizes[-1]                                    # the region past the last tensor
-            ok = ok and pool_blocks_equal(np.arange(cfg.num_blocks), end // bb, cfg.num_blocks, skip_below=end)
+            used = {}                                                              # weight bytes per strip (one strip if block-major)
+            for st_, sz, off, cid, coff in pieces:                                 # every tensor
+                content.fill_device(stage.data_ptr(), 1, sz, 0x5EED0002, cid0=cid, table_ptr=wtab.data_ptr(), byte_offset=coff)
+                at = device_offset(off)
+                ok = ok and torch.equal(pool_t[at:at + sz], stage[:sz])
+                l = off // strip if layer_stride else 0
+                used[l] = max(used.get(l, 0), off - l * strip * bool(layer_stride) + sz)
+            if not layer_stride:
+                ok = ok and pool_blocks_equal(cid_x, 0, cfg.boundary)              # moved and kept KV
+                end = region0 + used[0]                                            # the region past the last tensor
+                ok = ok and pool_blocks_equal(np.arange(cfg.num_blocks), end // bb, cfg.num_blocks, skip_below=end)
+            else:
+                scratch = torch.empty(layer_stride, dtype=torch.uint8, device=dev)
+                cid_d = torch.from_numpy(cid_x).to(dev)
+                for l in range(cfg.num_layers):                                    # slab by slab: KV below b, the strip's tail
+                    content.fill_device(scratch.data_ptr(), cfg.num_blocks, tile, cfg.seed, cids_ptr=cid_d.data_ptr(),
+                                        table_ptr=tptr, byte_offset=l * tile)
+                    slab = pool_t[l * layer_stride:(l + 1) * layer_stride]
+                    tail = cfg.boundary * tile + used.get(l, 0)
+                    ok = ok and torch.equal(slab[:cfg.boundary * tile], scratch[:cfg.boundary * tile])
+                    ok = ok and torch.equal(slab[tail:], scratch[tail:])
+                del scratch
             return bool(ok)
 
         checks = {"weights_materialize (gated)": verified(overlapped),
@@ -609,7 +653,9 @@ def main():
         if not all(checks.values()):
             print(f"bench.py: byte check of the overlapped weight paths failed: {checks}", file=sys.stderr)
             sys.exit(1)
-        out["materialize"] = {"workload": "configs[2]: 225 bf16 tensors, 15,009,316,864 B from pinned host memory",
+        out["materialize"] = {"workload": f"configs[2]: {len(pieces)} bf16 tensors, 15,009,316,864 B from pinned host memory"
+                                          + (" (layer-major pool: placed strip by strip, embedding rows in 32 slices)"
+                                             if layer_stride else ""),
                               "h2d_ms": round(t_copy, 2), "h2d_GBps": round(total / t_copy / 1e6, 2),
                               "link_peak_GBps": LINK_PEAK_GBPS,
                               "link_measured_plain_copy_GBps": round(n_plain / t_plain / 1e6, 2),
@@ -621,7 +667,7 @@ def main():
                               "verified": True,
                               "verified_paths": sorted(checks),
                               "verified_how": "one more untimed run of each path on a freshly generated pool; tables, every "
-                                              "block below the boundary, all 225 tensors and the region's tail compared "
+                                              "block below the boundary, every tensor and the region's tail compared "
                                               "byte for byte with the relocation rule written out in numpy"}
         host_weights = (host, starts, sizes, offs)
         if args.no_cpu_baseline:

@@ -237,8 +237,10 @@ typedef struct wm_piece {
  * kv_compact has read it.  live_host [host] is the bitmap kv_plan_reclaim was
  * given (before the move).  Tensors are walked in the caller's order and cut
  * at block boundaries; runs that lie wholly in free blocks become early pieces
- * until early_bytes (0 = 128 MiB) have been collected; all other bytes become
- * late pieces, one per tensor remainder run.  Host arithmetic only.
+ * until early_bytes have been collected (0 = the library's own policy: 128 MiB,
+ * and only runs of at least 2 MiB, below which a request costs more than it
+ * hides); all other bytes become late pieces, one per tensor remainder run.
+ * Host arithmetic only.
  * In a layer-major pool the unit is a block's tile in one strip: region offset
  * x lies in the tile of block boundary + (x mod strip bytes) / tile_bytes.
  * Writes at most `capacity` pieces to out [host] (early pieces first) and the

@@ -22,6 +22,12 @@ constexpr uint64_t kChunkBytes = 4ull << 30;     // bound on one DMA request (ea
 constexpr uint64_t kDefaultEarly = 128ull << 20;  // early bytes when the caller passes 0: about what the link
                                                  // carries during a few ms of block copy; every piece
                                                  // costs ~10 us of request overhead, so more loses
+constexpr uint64_t kMinEarlyPiece = 2ull << 20;   // with the default budget, a free run shorter than this stays
+                                                  // late: an early piece adds two request boundaries, each of
+                                                  // which idles the link for 10-45 us (0.6-2.6 MB of link time).
+                                                  // Measured on the 8B-shaped pool kept layer-major (64 KiB
+                                                  // tiles): every free tile early 284 ms, runs >= 512 KiB 271 ms,
+                                                  // gated 269 ms in the same runs
 
 struct Region {
   bool layer_major;
@@ -133,7 +139,7 @@ inline bool was_live(const uint64_t* live, uint64_t block) { return (live[block 
 // (at % strip_bytes) / tile_bytes (strips are whole tiles, and a tensor never
 // leaves its strip).
 void schedule(const Region& r, uint32_t boundary, const uint64_t* live, const wm_tensor* tensors,
-              uint32_t n_tensors, uint64_t early_budget, std::vector<wm_piece>* early,
+              uint32_t n_tensors, uint64_t early_budget, uint64_t min_early_piece, std::vector<wm_piece>* early,
               std::vector<wm_piece>* late) {
   const uint64_t unit = r.layer_major ? r.tile_bytes : r.block_bytes;
   auto block_of = [&](uint64_t at) -> uint64_t {
@@ -156,14 +162,20 @@ void schedule(const Region& r, uint32_t boundary, const uint64_t* live, const wm
         if (ready) collected += next_end - end;
         end = next_end;
       }
-      wm_piece p;
-      p.tensor = i;
-      p.early = ready ? 1u : 0u;
-      p.src_offset = pos;
-      p.dst_offset = at;
-      p.bytes = end - pos;
-      (ready ? early : late)->push_back(p);
-      if (ready) early_total += p.bytes;
+      const bool take_early = ready && end - pos >= min_early_piece;
+      if (!take_early && !late->empty() && late->back().tensor == i &&
+          late->back().src_offset + late->back().bytes == pos) {
+        late->back().bytes += end - pos;  // continues the late piece in front of it
+      } else {
+        wm_piece p;
+        p.tensor = i;
+        p.early = take_early ? 1u : 0u;
+        p.src_offset = pos;
+        p.dst_offset = at;
+        p.bytes = end - pos;
+        (take_early ? early : late)->push_back(p);
+      }
+      if (take_early) early_total += end - pos;
       pos = end;
     }
   }
@@ -208,7 +220,8 @@ extern "C" int weights_materialize_schedule(const kv_pool_desc* pool, uint32_t b
     if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
     if (r.block_bytes == 0) return KV_E_RANGE;
     std::vector<wm_piece> early, late;
-    schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
+    schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly,
+             early_bytes ? 0 : kMinEarlyPiece, &early, &late);
     const size_t total = early.size() + late.size();
     if (total > 0xFFFFFFFFull) return KV_E_RANGE;
     *n_out = (uint32_t)total;
@@ -230,7 +243,8 @@ extern "C" int weights_materialize_pipelined(const kv_pool_desc* pool, uint32_t 
     if (live_host == nullptr && pool->num_blocks != 0) return KV_E_NULL;
     if (r.block_bytes == 0) return KV_E_RANGE;
     std::vector<wm_piece> early, late;
-    schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly, &early, &late);
+    schedule(r, boundary, live_host, tensors, n_tensors, early_bytes ? early_bytes : kDefaultEarly,
+             early_bytes ? 0 : kMinEarlyPiece, &early, &late);
     hipStream_t s = (hipStream_t)copy_stream;
     Requests requests(s);
     for (const wm_piece& p : early) {

@@ -231,6 +231,38 @@ def test_materialize_schedule_in_a_layer_major_pool():
     assert e.value.code == wk.KV_E_TOOBIG
 
 
+def test_default_schedule_sends_no_early_piece_that_costs_more_than_it_hides():
+    """With the library's own policy (early_bytes = 0) a free run below 2 MiB stays late; an explicit
+    budget takes every free run."""
+    import numpy as np
+    from synth import bitmap_from_ids
+    nb, b = 4096, 2048
+    rs = np.random.default_rng(9)
+    live_bits = rs.random(nb) < 0.5
+    live = bitmap_from_ids(np.flatnonzero(live_bits), nb)
+    for layers, tile, stride in ((1, 2 << 20, 0), (4, 65536, nb * 65536), (1, 65536, 0)):
+        pool = wk.pool_desc(FAKE, nb, layers, tile, stride)
+        strip = (nb - b) * tile * (1 if stride else layers)
+        tensors = [(FAKE, strip - 4096, 4096)] + ([(FAKE, strip // 2, strip + 65536)] if stride else [])
+        default = wk.weights_materialize_schedule(pool, b, live, tensors)
+        explicit = wk.weights_materialize_schedule(pool, b, live, tensors, early_bytes=128 << 20)
+        for pieces in (default, explicit):                   # both partition every tensor in order
+            for i, (_, nbytes, off) in enumerate(tensors):
+                pos = 0
+                for _, _, so, do, n in sorted((p for p in pieces if p[0] == i), key=lambda p: p[2]):
+                    assert so == pos and do == off + so and n > 0
+                    pos += n
+                assert pos == nbytes
+        assert all(n >= 2 << 20 for _, early, _, _, n in default if early)
+        if tile >= 2 << 20:
+            assert any(early for _, early, _, _, _ in default)
+        else:
+            assert sum(1 for p in default if p[1]) < sum(1 for p in explicit if p[1])
+            assert any(n < 2 << 20 for _, early, _, _, n in explicit if early)
+            lates = [p for p in default if not p[1]]
+            assert len(lates) <= len(tensors) + 2 * sum(1 for p in default if p[1])   # late runs are merged again
+
+
 def test_grow_in_a_layer_major_pool_matches_oracle(oracle):
     import numpy as np
     nb, layers, tile = 50, 4, 128

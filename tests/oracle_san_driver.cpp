@@ -12,6 +12,12 @@ int oracle_plan(const uint64_t*, uint32_t, uint32_t, int32_t*, int32_t*, int32_t
 int oracle_compact(uint8_t*, uint64_t, const int32_t*, const int32_t*, uint32_t);
 int64_t oracle_remap(int32_t*, uint64_t, const int32_t*, uint32_t);
 int oracle_materialize(uint8_t*, uint64_t, uint64_t, const oracle_tensor*, uint32_t);
+int oracle_compact_layer_major(uint8_t*, uint64_t, uint32_t, uint64_t, const int32_t*, const int32_t*, uint32_t);
+int oracle_materialize_strips(uint8_t*, uint64_t, uint32_t, uint32_t, uint32_t, uint64_t, const oracle_tensor*, uint32_t);
+int64_t oracle_grow(uint64_t, uint32_t, uint32_t, uint32_t, const oracle_tensor*, uint32_t, uint8_t*, uint64_t*);
+int64_t oracle_grow_strips(uint64_t, uint32_t, uint32_t, uint64_t, uint32_t, uint32_t, const oracle_tensor*, uint32_t,
+                           uint8_t*, uint64_t*);
+int oracle_vmm_select(const uint64_t*, uint32_t, uint32_t, int32_t*);
 }
 
 static uint64_t state = 12345;
@@ -53,6 +59,29 @@ int main() {
         oracle_tensor t[2] = {{w0.data(), 16, 0}, {w1.data(), room - 16, 16}};
         if (oracle_materialize(pool.data(), pool.size(), region, t, 2) != 0) return 4;
       }
+      // the same plan on a layer-major pool of exact size (3 slabs, the last one unpadded), weights
+      // at the start of the first strip and up to the last byte of the last one, and the reverse switch
+      const uint64_t tile = 16, layers = 3, stride = (uint64_t)nb * tile + 32;
+      std::vector<uint8_t> lm((layers - 1) * stride + (uint64_t)nb * tile);
+      for (auto& x : lm) x = (uint8_t)next();
+      if (oracle_compact_layer_major(lm.data(), tile, layers, stride, src.data(), dst.data(), n) != 0) return 5;
+      const uint64_t strip = (uint64_t)(nb - b) * tile;
+      if (strip >= 32) {
+        std::vector<uint8_t> w0(16, 7), w1(strip - 16, 9);
+        oracle_tensor t[2] = {{w0.data(), 16, 0}, {w1.data(), strip - 16, (layers - 1) * strip + 16}};
+        if (oracle_materialize_strips(lm.data(), tile, layers, nb, b, stride, t, 2) != 0) return 6;
+        std::vector<uint8_t> ev(2);
+        std::vector<uint64_t> no(2);
+        if (oracle_grow_strips(tile, layers, nb, stride, b, b + (nb - b) / 2, t, 2, ev.data(), no.data()) < 0) return 7;
+        oracle_tensor flat[2] = {{nullptr, 16, 0}, {nullptr, strip - 16, 16}};
+        if (oracle_grow(tile, nb, b, nb, flat, 2, ev.data(), no.data()) < 0) return 8;
+      }
+      // page choice of the no-move variant: every free block, and one more than there are
+      uint32_t n_free = 0;
+      for (uint32_t i = 0; i < nb; ++i) n_free += !((live[i >> 6] >> (i & 63)) & 1);
+      std::vector<int32_t> ids(n_free ? n_free : 1);
+      if (oracle_vmm_select(live.data(), nb, n_free, ids.data()) != 0) return 9;
+      if (oracle_vmm_select(live.data(), nb, n_free + 1, ids.data()) != -7) return 10;
     }
   }
   std::puts("ok");

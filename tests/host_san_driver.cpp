@@ -125,6 +125,51 @@ int main() {
     }
     REQUIRE(seen == lost);
 
+    // the same through a layer-major description of the pool: extents inside strips
+    if (nb > b) {
+      const uint64_t strip = (uint64_t)(nb - b) * tile;
+      kv_pool_desc lm = {fake_dev, nb, layers, tile, ((uint64_t)nb * tile + 255) / 256 * 256 + 256 * below(3)};
+      std::vector<wm_tensor> ext;
+      for (uint32_t l = 0; l < layers; ++l) {
+        uint64_t pos = below(40);
+        while (pos < strip && ext.size() < 16) {
+          const uint64_t len = 1 + below(strip - pos < 5 * tile ? strip - pos : 5 * tile);
+          ext.push_back({host_bytes.data(), len > host_bytes.size() ? host_bytes.size() : len, l * strip + pos});
+          pos += len + below(3 * tile);
+        }
+      }
+      for (size_t i = ext.size(); i > 1; --i) std::swap(ext[i - 1], ext[below(i)]);
+      const uint32_t m = (uint32_t)ext.size();
+      uint32_t cnt = 0;
+      rc = weights_materialize_schedule(&lm, b, live.data(), ext.data(), m, early_budget, none.data(), 0, &cnt);
+      REQUIRE(rc == (cnt ? KV_E_TOOBIG : KV_OK));
+      std::vector<wm_piece> ps(cnt);
+      rc = weights_materialize_schedule(&lm, b, live.data(), ext.data(), m, early_budget, ps.data(), cnt, &cnt);
+      REQUIRE(rc == KV_OK);
+      std::vector<uint64_t> cov(m, 0);
+      for (uint32_t k = 0; k < cnt; ++k) {
+        const wm_piece& p = ps[k];
+        REQUIRE(p.tensor < m && p.bytes > 0 && p.dst_offset == ext[p.tensor].dst_offset + p.src_offset);
+        cov[p.tensor] += p.bytes;
+        if (p.early)
+          for (uint64_t t = (p.dst_offset % strip) / tile; t <= ((p.dst_offset + p.bytes - 1) % strip) / tile; ++t)
+            REQUIRE(!bit(live, b + t));  // only tiles of blocks that were free
+      }
+      for (uint32_t i = 0; i < m; ++i) REQUIRE(cov[i] == ext[i].bytes);
+      std::vector<uint8_t> ev(m);
+      std::vector<uint64_t> no(m);
+      const int64_t gone = kv_grow(&lm, b, nb2, ext.data(), m, ev.data(), no.data());
+      REQUIRE(gone >= 0);
+      const uint64_t back = (uint64_t)(nb2 - b) * tile, new_strip = (uint64_t)(nb - nb2) * tile;
+      for (uint32_t i = 0; i < m; ++i) {
+        const uint64_t l = ext[i].dst_offset / strip, within = ext[i].dst_offset % strip;
+        REQUIRE((ev[i] != 0) == (within < back));
+        if (within >= back) REQUIRE(no[i] == l * new_strip + within - back);
+      }
+      wm_tensor across = {host_bytes.data(), 2, strip - 1};
+      if (layers > 1) REQUIRE(weights_materialize(&lm, b, &across, 1, nullptr, nullptr) == KV_E_TOOBIG);
+    }
+
     // refused before any launch: an extent one byte too long, two that overlap
     if (n >= 1) {
       std::vector<wm_tensor> bad = tensors;

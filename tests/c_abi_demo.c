@@ -88,6 +88,39 @@ int main(void) {
   for (size_t i = 0; i < weight_bytes; ++i)
     if (after[(size_t)B * block_bytes + 256 + i] != 0xC3) return 11;
   if (kv_reserve_blocks(20480, 5120, 8, 32) != 5760) return 12;    /* Eq. 4 hand case */
+
+  /* The same reclaim once more from the original state, through the one-call entry points: kv_reclaim on
+   * the caller's workspace and kv_reclaim_static on the library's own.  Pool and tables must come out as
+   * they did above (below the boundary; above it the first run also placed weights). */
+  {
+    void *live_out_d, *state_d;
+    unsigned char* again = (unsigned char*)malloc(pool_bytes);
+    int32_t tables2[SEQS][WIDTH];
+    CHECK_HIP(hipMalloc(&live_out_d, sizeof live));
+    CHECK_HIP(hipMalloc(&state_d, sizeof(kv_plan_state)));
+    for (int variant = 0; variant < 2; ++variant) {
+      CHECK_HIP(hipMemcpy(pool_d, host_pool, pool_bytes, hipMemcpyHostToDevice));
+      CHECK_HIP(hipMemcpy(tables_d, before_tables, sizeof tables, hipMemcpyHostToDevice));
+      kv_plan_state st2;
+      if (variant == 0) {
+        CHECK_KV(kv_reclaim(&pool, &plan, (const uint64_t*)live_d, (int32_t*)tables_d, SEQS, WIDTH, compute));
+        CHECK_KV(kv_plan_fetch(&plan, compute, &st2));
+      } else {
+        CHECK_KV(kv_reclaim_static(&pool, B, (const uint64_t*)live_d, (uint64_t*)live_out_d, (int32_t*)tables_d, SEQS,
+                                   WIDTH, (kv_plan_state*)state_d, compute));
+        CHECK_HIP(hipStreamSynchronize(compute));
+        CHECK_HIP(hipMemcpy(&st2, state_d, sizeof st2, hipMemcpyDeviceToHost));
+      }
+      if (st2.status != KV_OK || st2.n_moves != st.n_moves || st2.n_bad_entries != 0) return 13;
+      CHECK_HIP(hipMemcpy(again, pool_d, pool_bytes, hipMemcpyDeviceToHost));
+      CHECK_HIP(hipMemcpy(tables2, tables_d, sizeof tables2, hipMemcpyDeviceToHost));
+      if (memcmp(tables2, tables, sizeof tables) != 0) return 14;
+      if (memcmp(again, after, (size_t)B * block_bytes) != 0) return 15;
+      if (memcmp(again + (size_t)B * block_bytes, host_pool + (size_t)B * block_bytes, pool_bytes - (size_t)B * block_bytes) != 0)
+        return 16;                                                 /* sources keep their bytes */
+    }
+    free(again);
+  }
   printf("c_abi_demo ok: %u blocks moved, version %s\n", st.n_moves, warmkv_version());
   return 0;
 }

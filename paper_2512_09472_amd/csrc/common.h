@@ -45,6 +45,18 @@ inline auto guarded(Body&& body) noexcept -> decltype(body()) {
   }
 }
 
+// The block copy numbers its work units with 32 bits.  True if a plan of `capacity` moves on this
+// pool stays below that whatever unit size the copy picks (its units are never below 32 KiB unless
+// the caller tunes them), so that a call that chains planner and copy can refuse before the planner
+// is launched what the copy would refuse after it.
+inline bool copy_units_fit(const kv_pool_desc& p, uint32_t capacity) {
+  const bool layer_major = p.layer_stride_bytes != 0;
+  const uint64_t segs = layer_major ? p.num_layers : 1u;
+  const uint64_t seg_bytes = layer_major ? p.tile_bytes : (uint64_t)p.num_layers * p.tile_bytes;
+  const uint64_t chunks = (seg_bytes + 32767u) / 32768u;
+  return segs * chunks * (uint64_t)capacity < (1ull << 31);
+}
+
 // Launch status without clearing an earlier sticky error of the caller's.
 inline int launch_rc() { return hip_rc(hipGetLastError()); }
 

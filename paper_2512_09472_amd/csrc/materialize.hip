@@ -332,7 +332,7 @@ extern "C" int kv_switch(const kv_switch_request* rq, kv_plan_state* result) {
     const kv_pool_desc* pool = rq->pool;
     const kv_plan* plan = rq->plan;
     if (pool->num_blocks != plan->num_blocks || plan->boundary > plan->num_blocks) return KV_E_RANGE;
-    if (!pool_extent_ok(*pool)) return KV_E_RANGE;
+    if (!pool_extent_ok(*pool) || !copy_units_fit(*pool, plan->capacity)) return KV_E_RANGE;
     if ((pool->tile_bytes % 16u) != 0 || ((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
     const uint64_t n_entries = (uint64_t)rq->num_seqs * rq->max_blocks_per_seq;
     if (n_entries != 0 && rq->tables == nullptr) return KV_E_NULL;

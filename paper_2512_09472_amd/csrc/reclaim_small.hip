@@ -243,7 +243,7 @@ extern "C" int kv_reclaim(const kv_pool_desc* pool, const kv_plan* plan, const u
   if (pool->num_blocks != nb || b > nb || nb > kMaxBlocks) return KV_E_RANGE;
   if (plan->capacity != (nb - b < b ? nb - b : b)) return KV_E_RANGE;
   if (plan->capacity != 0 && (plan->src == nullptr || plan->dst == nullptr)) return KV_E_NULL;
-  if (!pool_extent_ok(*pool)) return KV_E_RANGE;
+  if (!pool_extent_ok(*pool) || !copy_units_fit(*pool, plan->capacity)) return KV_E_RANGE;
   if ((pool->tile_bytes % kVec) != 0) return KV_E_ALIGN;
   const bool layer_major = pool->layer_stride_bytes != 0;
   if (layer_major && (pool->layer_stride_bytes % 256u != 0 ||

@@ -64,6 +64,7 @@ extern "C" int kv_reclaim_static(const kv_pool_desc* pool, uint32_t boundary, co
   if (need == 0 || need > kScratchBytes) return KV_E_TOOBIG;
   // everything the three steps would refuse is refused before the first launch
   if (!pool_extent_ok(*pool)) return KV_E_RANGE;
+  if (!copy_units_fit(*pool, nb - boundary < boundary ? nb - boundary : boundary)) return KV_E_RANGE;
   if ((pool->tile_bytes % 16u) != 0 || ((uintptr_t)pool->base % 256u) != 0) return KV_E_ALIGN;
   if (pool->layer_stride_bytes != 0 && (pool->layer_stride_bytes % 256u != 0 ||
                                         pool->layer_stride_bytes < (uint64_t)nb * pool->tile_bytes))

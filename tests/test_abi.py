@@ -414,6 +414,25 @@ def test_absurd_pool_sizes_are_refused():
         assert e.value.code == wk.KV_E_RANGE
 
 
+def test_chained_calls_refuse_too_many_copy_units_before_the_planner_runs():
+    """The block copy numbers its units with 32 bits; the calls that chain planner and copy check
+    that first, so that a refusal leaves nothing enqueued (they return before any HIP call here)."""
+    nb, b = 1 << 20, 1 << 19                      # 524 288 possible moves x 8192 units of a 256 MiB block = 2^32
+    plan = wk.kv_plan_bind(FAKE, wk.kv_plan_workspace_bytes(nb, b), nb, b)
+    pool = wk.pool_desc(FAKE + (1 << 30), nb, 1, 1 << 28)
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.kv_reclaim(pool, plan, FAKE + (1 << 29), FAKE + (1 << 28), 1, 4)
+    assert e.value.code == wk.KV_E_RANGE
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.kv_switch(pool, plan, FAKE + (1 << 29), FAKE + (1 << 28), 1, 4, [], 0, 0, FAKE)
+    assert e.value.code == wk.KV_E_RANGE
+    small_nb = 1 << 18                             # the static entry point's largest pool, blocks of 1 GiB
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.kv_reclaim_static(wk.pool_desc(FAKE + (1 << 30), small_nb, 1, 1 << 30), small_nb // 2, FAKE + (1 << 29),
+                             FAKE + (1 << 27), FAKE + (1 << 28), 1, 4, FAKE + (1 << 26))
+    assert e.value.code == wk.KV_E_RANGE
+
+
 def test_movers_in_front_counts_live_blocks_above_the_boundary():
     rs = np.random.default_rng(3)
     for nb, b in ((1, 0), (64, 64), (130, 70), (1000, 333), (5000, 4999)):

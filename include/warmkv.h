@@ -169,12 +169,13 @@ int kv_compact_launch(const kv_pool_desc* pool, const kv_plan* plan,
  * row-major, -1 = empty] becomes new_id[e].  Entries that name an id >= NB or
  * a block that was not live are left as they are and counted in
  * state.n_bad_entries (added to what is there).  Does nothing unless
- * state.status == KV_OK and state.bad_plan == 0.  (The engine goes on seeing one address space and
- * never learns that blocks moved: App. C.) */
+ * state.status == KV_OK and state.bad_plan == 0.  (The engine goes on seeing
+ * one address space and never learns that blocks moved: App. C.) */
 int kv_remap_tables(int32_t* tables, uint32_t num_seqs, uint32_t max_blocks_per_seq,
                     const kv_plan* plan, void* stream);
 
-/* The reclaim step as one call: kv_plan_reclaim, kv_compact and kv_remap_tables
+/* The reclaim step as one call (App. C, Fig. 4b steps 1-2, as the three calls
+ * above): kv_plan_reclaim, kv_compact and kv_remap_tables
  * on `stream`, with the same arguments, rules and results (all of the plan's
  * arrays and its header are written as the three calls write them).  A small
  * pool - at most 32 768 blocks, at most 16 384 table entries, at most 128 MiB

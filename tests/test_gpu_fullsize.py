@@ -6,10 +6,10 @@ oracle element by element.  The pool is checked in one of two modes, printed by
 every test:
 
 * full: where the host has room for a second copy of the pool (MemAvailable >=
-  pool + 16 GiB, pools up to 64 GiB), the initial pool is brought to pinned host
-  memory, the oracle's block copy (and weight copy) run on that buffer, and the
+  pool + 16 GiB; + 48 GiB for the 120 GiB pool, whose copy is too large to pin and
+  stays pageable), the initial pool is brought to host memory, the oracle's block copy (and weight copy) run on that buffer, and the
   device pool is compared with it byte for byte in 1 GiB slices.
-* lazy (always run as well; the only mode for the 120 GiB pool): block content is a
+* lazy (always run as well): block content is a
   pure function of a content id, the oracle's plan says which content id every
   block must hold afterwards, and the device generator re-creates each 1 GiB
   slab for a byte compare.  A sample of blocks of every kind is brought back to
@@ -53,17 +53,34 @@ _host_pool_cache = []
 PINNED_BUDGET = 60 << 30     # host memory this module keeps pinned at once (the box refused 80 GiB)
 
 
+class PageableHostBuffer:
+    """Plain host memory with the interface of synth.content.PinnedHostBuffer, for a pool copy too
+    large to pin (copies to and from it are staged by the runtime and slower)."""
+
+    def __init__(self, nbytes: int):
+        self.nbytes = nbytes
+        self.array = np.empty(nbytes, dtype=np.uint8)
+        self.ptr = self.array.ctypes.data
+
+    def free(self) -> None:
+        self.array = None
+        self.ptr = None
+
+
 def _pinned_host_pool(nbytes: int, other_pinned: int = 0):
-    """A pinned host buffer (synth.content.PinnedHostBuffer) of nbytes for the oracle's copy of a
-    pool, or None where the host has no room for it (then only the lazy comparison runs).  A buffer
-    of the same size is reused; one of another size is given back first."""
-    if nbytes > FULL_MODE_MAX_POOL or nbytes + other_pinned > max(PINNED_BUDGET, nbytes):
-        return None
+    """A host buffer of nbytes for the oracle's copy of a pool - pinned (synth.content.PinnedHostBuffer)
+    up to 64 GiB, pageable above that - or None where the host has no room for it (then only the lazy
+    comparison runs).  A buffer of the same size is reused; one of another size is given back first."""
     if _host_pool_cache and _host_pool_cache[0].nbytes == nbytes:
         return _host_pool_cache[0]
     while _host_pool_cache:
         _host_pool_cache.pop().free()
-    if _mem_available() < nbytes + (16 << 30):
+    if nbytes > FULL_MODE_MAX_POOL:
+        if _mem_available() < nbytes + (48 << 30):
+            return None
+        _host_pool_cache.append(PageableHostBuffer(nbytes))
+        return _host_pool_cache[0]
+    if nbytes + other_pinned > max(PINNED_BUDGET, nbytes) or _mem_available() < nbytes + (16 << 30):
         return None
     try:
         _host_pool_cache.append(content.PinnedHostBuffer(nbytes))

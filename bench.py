@@ -588,6 +588,29 @@ def main():
             wk.kv_switch(pool, plan, live_d, tables_d, w.tables.shape[0], w.tables.shape[1], tensors, s, cs,
                          done.cuda_event, live_host=w.live, front_done=front_done.cuda_event)
 
+        copy_stream2 = torch.cuda.Stream()
+
+        def one_call_two_streams():
+            with torch.cuda.stream(stream):
+                tables_d.copy_(tables0_d, non_blocking=True)
+            wk.kv_switch(pool, plan, live_d, tables_d, w.tables.shape[0], w.tables.shape[1], tensors, s, cs,
+                         done.cuda_event, live_host=w.live, front_done=front_done.cuda_event,
+                         copy_stream2=copy_stream2.cuda_stream)
+
+        # a checkpoint whose tensors do not continue each other in host memory: every tensor (cut at
+        # 64 MiB) is a request of its own, listed so that neighbours never merge
+        split = []
+        for a_, n_, o_ in tensors:
+            for c0 in range(0, n_, 64 << 20):
+                split.append((a_ + c0, min(64 << 20, n_ - c0), o_ + c0))
+        split = split[0::2] + split[1::2]
+
+        def copy_split_one_stream():
+            wk.weights_materialize(pool, cfg.boundary, split, cs, None)
+
+        def copy_split_two_streams():
+            wk.weights_materialize_streams(pool, cfg.boundary, split, [cs, copy_stream2.cuda_stream])
+
         # the link's measured ceiling: one plain pinned-to-device copy of 4 GiB into the same region
         n_plain = min(4 << 30, total)
 
@@ -606,6 +629,9 @@ def main():
         done.record(stream)                # torch creates a HIP event on its first record
         front_done.record(stream)
         t_switch = timed(one_call)
+        t_switch2 = timed(one_call_two_streams)
+        t_split1 = timed(copy_split_one_stream)
+        t_split2 = timed(copy_split_two_streams)
 
         # Byte check of the overlapped paths, outside every timed region: each runs once more on a
         # freshly generated pool (the timed replays above had weights where KV should be), then
@@ -648,7 +674,8 @@ def main():
 
         checks = {"weights_materialize (gated)": verified(overlapped),
                   "weights_materialize_pipelined": verified(pipelined),
-                  "kv_switch (front first)": verified(one_call)}
+                  "kv_switch (front first)": verified(one_call),
+                  "kv_switch (front first, two copy streams)": verified(one_call_two_streams)}
         del stage
         if not all(checks.values()):
             print(f"bench.py: byte check of the overlapped weight paths failed: {checks}", file=sys.stderr)
@@ -664,6 +691,9 @@ def main():
                               "overlapped_ms": round(t_overlap, 2),
                               "block_pipelined_ms": round(t_pipe, 2),
                               "kv_switch_one_call_ms": round(t_switch, 2),
+                              "kv_switch_one_call_two_copy_streams_ms": round(t_switch2, 2),
+                              "h2d_unmergeable_requests": {"requests": len(split), "one_stream_ms": round(t_split1, 2),
+                                                           "two_streams_ms": round(t_split2, 2)},
                               "verified": True,
                               "verified_paths": sorted(checks),
                               "verified_how": "one more untimed run of each path on a freshly generated pool; tables, every "

@@ -300,6 +300,21 @@ int weights_materialize_front(const kv_pool_desc* pool, uint32_t boundary, uint6
                               const wm_tensor* tensors, uint32_t n_tensors,
                               void* copy_stream, void* front_done, void* compaction_done);
 
+/* The weight stream over several copy streams.  As weights_materialize_front
+ * (front_bytes = 0 and front_done = NULL: as weights_materialize), but the
+ * host-to-device requests are dealt out in turn to copy_streams[0..n_streams)
+ * [host array of hipStream_t, 1 to 4 streams], each of which waits for the
+ * events as the single stream would.  Streams are served by different DMA
+ * engines, so the next request is set up while the previous one still runs and
+ * the link does not idle at request boundaries: what a checkpoint of many
+ * tensors that do not continue each other in host memory loses on one stream
+ * (10-45 us per tensor).  The same bytes arrive; the caller synchronises every
+ * stream it passed. */
+int weights_materialize_streams(const kv_pool_desc* pool, uint32_t boundary, uint64_t front_bytes,
+                                const wm_tensor* tensors, uint32_t n_tensors,
+                                void* const* copy_streams, uint32_t n_streams,
+                                void* front_done, void* compaction_done);
+
 /* One request for the whole hand-over (App. C, Fig. 4b steps 1-3). */
 typedef struct kv_switch_request {
   const kv_pool_desc* pool;
@@ -319,6 +334,8 @@ typedef struct kv_switch_request {
   void*               compaction_done;  /* hipEvent_t created by the caller; recorded by this call    */
   void*               front_done;    /* second hipEvent_t of the caller's, or NULL; with live_host it
                                         selects the front-first weight stream (see below)            */
+  void*               copy_stream2;  /* a second copy stream, or NULL: weight requests alternate
+                                        between the two (see weights_materialize_streams)            */
 } kv_switch_request;
 
 /* The hand-over as one call: plan, block copy and table rewrite on

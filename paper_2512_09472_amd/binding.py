@@ -34,7 +34,7 @@ _NAMES = {KV_OK: "KV_OK", KV_E_NULL: "KV_E_NULL", KV_E_RANGE: "KV_E_RANGE", KV_E
 
 EXPORTS = ("kv_plan_workspace_bytes", "kv_plan_bind", "kv_plan_reclaim", "kv_compact", "kv_compact_launch",
            "kv_remap_tables", "kv_reclaim", "kv_plan_fetch", "weights_materialize", "weights_materialize_schedule",
-           "weights_materialize_pipelined", "kv_compact_moves", "kv_compact_layers", "kv_movers_in_front", "weights_materialize_front",
+           "weights_materialize_pipelined", "kv_compact_moves", "kv_compact_layers", "kv_movers_in_front", "weights_materialize_front", "weights_materialize_streams",
            "kv_switch", "kv_reclaim_static", "kv_reserve_blocks", "kv_grow", "kv_vmm_pool_create", "kv_vmm_kv_base", "kv_vmm_slot_base",
            "kv_vmm_reclaim", "kv_vmm_reclaim_load", "kv_vmm_lent", "kv_vmm_restore", "kv_vmm_pool_destroy", "ws_predict_load", "ws_replica_scores",
            "ws_place_replicas", "warmkv_version", "warmkv_build_id")
@@ -84,7 +84,8 @@ class kv_switch_request(Structure):
                 ("live_host", c_void_p), ("tables", c_void_p), ("num_seqs", c_uint32),
                 ("max_blocks_per_seq", c_uint32), ("tensors", POINTER(wm_tensor)), ("n_tensors", c_uint32),
                 ("reserved", c_uint32), ("early_bytes", c_uint64), ("compute_stream", c_void_p),
-                ("copy_stream", c_void_p), ("compaction_done", c_void_p), ("front_done", c_void_p)]
+                ("copy_stream", c_void_p), ("compaction_done", c_void_p), ("front_done", c_void_p),
+                ("copy_stream2", c_void_p)]
 
 
 class ws_model(Structure):
@@ -175,6 +176,9 @@ def load():
     L.weights_materialize_front.restype = c_int
     L.weights_materialize_front.argtypes = [POINTER(kv_pool_desc), c_uint32, c_uint64, POINTER(wm_tensor), c_uint32,
                                             c_void_p, c_void_p, c_void_p]
+    L.weights_materialize_streams.restype = c_int
+    L.weights_materialize_streams.argtypes = [POINTER(kv_pool_desc), c_uint32, c_uint64, POINTER(wm_tensor), c_uint32,
+                                              POINTER(c_void_p), c_uint32, c_void_p, c_void_p]
     L.kv_switch.restype = c_int
     L.kv_switch.argtypes = [POINTER(kv_switch_request), POINTER(kv_plan_state)]
     L.kv_reclaim_static.restype = c_int
@@ -339,9 +343,19 @@ def weights_materialize_front(pool: kv_pool_desc, boundary: int, front_bytes: in
                                             _ptr(front_done), _ptr(compaction_done)))
 
 
+def weights_materialize_streams(pool: kv_pool_desc, boundary: int, tensors, copy_streams, front_bytes: int = 0,
+                                front_done=None, compaction_done=None) -> None:
+    """The weight stream dealt out over several copy streams (a sequence of 1 to 4)."""
+    arr, n = _tensor_array(tensors)
+    streams = (c_void_p * max(1, len(copy_streams)))(*[_ptr(x) for x in copy_streams])
+    _check("weights_materialize_streams",
+           load().weights_materialize_streams(byref(pool), boundary, front_bytes, arr, n, streams, len(copy_streams),
+                                              _ptr(front_done), _ptr(compaction_done)))
+
+
 def kv_switch(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int, max_blocks_per_seq: int, tensors,
               compute_stream, copy_stream, compaction_done, live_host=None, early_bytes: int = 0,
-              front_done=None) -> kv_plan_state:
+              front_done=None, copy_stream2=None) -> kv_plan_state:
     """The whole hand-over in one call; returns the plan's header.  Raises WarmKVError (KV_E_NOSPACE) if the
     request is infeasible, in which case nothing was moved or sent."""
     arr, n = _tensor_array(tensors)
@@ -350,7 +364,7 @@ def kv_switch(pool: kv_pool_desc, plan: kv_plan, live_in, tables, num_seqs: int,
         live_host_ptr = live_host.ctypes.data if hasattr(live_host, "ctypes") else _ptr(live_host)
     rq = kv_switch_request(ctypes.pointer(pool), ctypes.pointer(plan), _ptr(live_in), live_host_ptr, _ptr(tables),
                            num_seqs, max_blocks_per_seq, arr, n, 0, early_bytes, _ptr(compute_stream),
-                           _ptr(copy_stream), _ptr(compaction_done), _ptr(front_done))
+                           _ptr(copy_stream), _ptr(compaction_done), _ptr(front_done), _ptr(copy_stream2))
     st = kv_plan_state()
     _check("kv_switch", load().kv_switch(byref(rq), byref(st)))
     return st

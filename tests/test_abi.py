@@ -75,7 +75,7 @@ def test_struct_sizes_match_the_header():
     assert ctypes.sizeof(binding.kv_compact_tuning) == 16
     assert ctypes.sizeof(binding.wm_tensor) == 24
     assert ctypes.sizeof(binding.wm_piece) == 32
-    assert ctypes.sizeof(binding.kv_switch_request) == 104
+    assert ctypes.sizeof(binding.kv_switch_request) == 112
 
 
 def test_workspace_and_bind():

@@ -334,7 +334,7 @@ class WeightedPool:
         self.tensors = [(self.host.data_ptr() + st, sz, off) for st, sz, off in zip(self.starts, self.sizes, self.offs)]
         self.pool = wk.pool_desc(self.pool_t, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
         self.live_d = gh.to_dev(self.w.live)
-        self.s_compute, self.s_copy = torch.cuda.Stream(), torch.cuda.Stream()
+        self.s_compute, self.s_copy, self.s_copy2 = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
         self.done, self.front = torch.cuda.Event(), torch.cuda.Event()
         self.done.record(self.s_compute)           # torch creates the HIP event on its first record
         self.front.record(self.s_compute)
@@ -515,7 +515,7 @@ def test_full_size_reclaim_with_weights(weighted):
 # reclaimed region for about 3 ms while the weight stream is already writing into it, so an event
 # wait that is missing or attached to the wrong piece would leave weight bytes in a moved block (or
 # stale KV in a tensor), which the whole-pool compare against the oracle sees.
-@pytest.mark.parametrize("order", ["forward", "reverse"])
+@pytest.mark.parametrize("order", ["forward", "reverse", "reverse_two_copy_streams"])
 @pytest.mark.parametrize("mode", ["front", "block"])
 def test_full_size_switch_in_one_call(weighted, mode, order):
     """kv_switch with the front-first and with the block-pipelined weight stream.  `reverse` lists the
@@ -528,7 +528,8 @@ def test_full_size_switch_in_one_call(weighted, mode, order):
     wp.fresh_pool()
     st = wk.kv_switch(wp.pool, wp.dp.plan, wp.live_d, wp.tables_d, w.tables.shape[0], w.tables.shape[1], tensors,
                       wp.s_compute.cuda_stream, wp.s_copy.cuda_stream, wp.done.cuda_event, live_host=w.live,
-                      front_done=wp.front.cuda_event if mode == "front" else None)
+                      front_done=wp.front.cuda_event if mode == "front" else None,
+                      copy_stream2=wp.s_copy2.cuda_stream if order.endswith("two_copy_streams") else None)
     assert st.status == 0 and st.n_moves == wp.p.n_moves
     wp.check(f"kv_switch {mode} {order}")
 
@@ -586,14 +587,15 @@ def test_full_size_block_pipelined_weight_stream(weighted):
         wp.check(f"block-pipelined, early budget {early}")
 
 
-@pytest.mark.parametrize("path", ["gated", "switch_front", "switch_front_reverse", "switch_block", "front_3_strips_reverse"])
+@pytest.mark.parametrize("path", ["gated", "switch_front", "switch_front_reverse", "switch_block", "front_3_strips_reverse",
+                                  "switch_front_two_copy_streams", "front_3_strips_reverse_three_copy_streams"])
 def test_full_size_layer_major_weight_paths(weighted, path):
     """The 8B-shaped pool kept layer-major (32 slabs of 1.25 GiB, strips of 512 MiB), with the same
     15 GB of weights placed strip by strip, the table rewrite, and every overlapped weight path."""
     wp = weighted
     cfg, w = wp.cfg, wp.w
     s, cs = wp.s_compute.cuda_stream, wp.s_copy.cuda_stream
-    tensors = wp.lm_tensors[::-1] if path.endswith("reverse") else wp.lm_tensors
+    tensors = wp.lm_tensors[::-1] if "reverse" in path else wp.lm_tensors
     wp.expect("layer")
     wp.fresh_pool("layer")
     if path == "gated":
@@ -605,9 +607,10 @@ def test_full_size_layer_major_weight_paths(weighted, path):
     elif path.startswith("switch"):
         st = wk.kv_switch(wp.pool_lm, wp.dp.plan, wp.live_d, wp.tables_d, w.tables.shape[0], w.tables.shape[1], tensors,
                           s, cs, wp.done.cuda_event, live_host=w.live,
-                          front_done=wp.front.cuda_event if "front" in path else None)
+                          front_done=wp.front.cuda_event if "front" in path else None,
+                          copy_stream2=wp.s_copy2.cuda_stream if path.endswith("two_copy_streams") else None)
         assert st.status == 0 and st.n_moves == wp.p.n_moves
-    else:
+    elif path.startswith("front_3_strips"):
         front_bytes = 2 * wp.strip + 4096           # needs the first three strips
         wk.kv_plan_reclaim(wp.live_d, wp.dp.plan, s)
         wk.kv_compact_layers(wp.pool_lm, wp.dp.plan, 0, 3, s)
@@ -615,6 +618,11 @@ def test_full_size_layer_major_weight_paths(weighted, path):
         wk.kv_compact_layers(wp.pool_lm, wp.dp.plan, 3, 0xFFFFFFFF, s)
         wp.done.record(wp.s_compute)
         wk.kv_remap_tables(wp.tables_d, w.tables.shape[0], w.tables.shape[1], wp.dp.plan, s)
-        wk.weights_materialize_front(wp.pool_lm, cfg.boundary, front_bytes, tensors, cs, wp.front.cuda_event,
-                                     wp.done.cuda_event)
+        if path.endswith("three_copy_streams"):
+            third = torch.cuda.Stream()
+            wk.weights_materialize_streams(wp.pool_lm, cfg.boundary, tensors, [cs, wp.s_copy2.cuda_stream, third.cuda_stream],
+                                           front_bytes, wp.front.cuda_event, wp.done.cuda_event)
+        else:
+            wk.weights_materialize_front(wp.pool_lm, cfg.boundary, front_bytes, tensors, cs, wp.front.cuda_event,
+                                         wp.done.cuda_event)
     wp.check_layer_major(f"layer-major {path}")

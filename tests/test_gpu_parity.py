@@ -1011,6 +1011,82 @@ def test_front_first_weight_stream_matches_oracle(oracle):
         assert np.array_equal(pool_dev.cpu().numpy(), want), front_blocks
 
 
+@pytest.mark.parametrize("n_streams", [1, 2, 3, 4])
+def test_weight_stream_over_several_copy_streams_matches_oracle(oracle, n_streams):
+    """weights_materialize_streams deals the requests out over 1-4 streams; the pool must hold what the
+    oracle's copies produce, with the mark anywhere, the block copy running beside it, and tensors
+    that cannot be merged (separate pinned buffers, gaps between them in the region)."""
+    cfg = CONFIGS[2].scaled(num_blocks=640, num_layers=2, num_seqs=48)
+    w = make_workload(cfg)
+    bb = cfg.block_bytes
+    pool0 = gh.host_pool(cfg, gh.content_table(cfg))
+    region = (cfg.num_blocks - cfg.boundary) * bb
+    rs = np.random.default_rng(n_streams)
+    sizes, offs, at = [], [], 0
+    while at + 3 * bb < region and len(sizes) < 60:
+        sz = int(rs.integers(1, 3 * bb // 16)) * 16
+        sizes.append(sz)
+        offs.append(at)
+        at += sz + int(rs.integers(0, 3)) * 256
+    hosts = []
+    for i, sz in enumerate(sizes):
+        h = torch.empty(sz, dtype=torch.uint8, pin_memory=True)
+        h.numpy()[:] = content.item_bytes_host(0xD0, i, -(-sz // 8) * 8, None)[:sz]
+        hosts.append(h)
+    order = rs.permutation(len(sizes)).tolist()
+    tensors = [(hosts[i], sizes[i], offs[i]) for i in order]
+    p = oracle.plan(w.live, cfg.num_blocks, cfg.boundary)
+    want_pool, want_tables = pool0.copy(), w.tables.copy()
+    oracle.compact(want_pool, bb, p)
+    assert oracle.remap(want_tables, p) == 0
+    assert oracle.materialize(want_pool, cfg.boundary * bb, [(hosts[i].numpy(), offs[i]) for i in order]) == 0
+    s_compute = torch.cuda.Stream()
+    copies = [torch.cuda.Stream() for _ in range(n_streams)]
+    done, front_done = torch.cuda.Event(), torch.cuda.Event()
+    done.record(s_compute)
+    front_done.record(s_compute)
+    live_dev = gh.to_dev(w.live)
+    for front_blocks in (0, 5, cfg.num_blocks):
+        front_bytes = front_blocks * bb + (4096 if front_blocks == 5 else 0)
+        head = wk.kv_movers_in_front(w.live, cfg.num_blocks, cfg.boundary, -(-front_bytes // bb))
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+        dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+        torch.cuda.synchronize()
+        wk.kv_plan_reclaim(live_dev, dp.plan, s_compute.cuda_stream)
+        wk.kv_compact_moves(pool, dp.plan, 0, head, s_compute.cuda_stream)
+        front_done.record(s_compute)
+        wk.kv_compact_moves(pool, dp.plan, head, 1 << 31, s_compute.cuda_stream)
+        done.record(s_compute)
+        wk.weights_materialize_streams(pool, cfg.boundary, tensors, [c.cuda_stream for c in copies], front_bytes,
+                                       front_done.cuda_event if front_blocks else None, done.cuda_event)
+        torch.cuda.synchronize()
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), (n_streams, front_blocks)
+    # kv_switch with a second copy stream, in its three modes
+    for mode in ("gated", "block", "front"):
+        pool_dev = torch.from_numpy(pool0).to(gh.dev())
+        pool = wk.pool_desc(pool_dev, cfg.num_blocks, cfg.num_layers, cfg.tile_bytes)
+        tables_dev = torch.from_numpy(w.tables).to(gh.dev())
+        dp = gh.DevicePlan(cfg.num_blocks, cfg.boundary)
+        torch.cuda.synchronize()
+        st = wk.kv_switch(pool, dp.plan, live_dev, tables_dev, *w.tables.shape, tensors, s_compute.cuda_stream,
+                          copies[0].cuda_stream, done.cuda_event, live_host=None if mode == "gated" else w.live,
+                          early_bytes=(1 << 40) if mode == "block" else 0,
+                          front_done=front_done.cuda_event if mode == "front" else None,
+                          copy_stream2=copies[-1].cuda_stream if n_streams > 1 else None)
+        assert st.status == 0 and st.n_moves == p.n_moves
+        torch.cuda.synchronize()
+        _compare_plan(dp, p)
+        assert np.array_equal(tables_dev.cpu().numpy(), want_tables), mode
+        assert np.array_equal(pool_dev.cpu().numpy(), want_pool), mode
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.weights_materialize_streams(pool, cfg.boundary, tensors, [c.cuda_stream for c in copies] * 5)
+    assert e.value.code == wk.KV_E_RANGE
+    with pytest.raises(wk.WarmKVError) as e:
+        wk.weights_materialize_streams(pool, cfg.boundary, tensors, [])
+    assert e.value.code == wk.KV_E_RANGE
+
+
 @pytest.mark.parametrize("pipelined", [False, True, "front"])
 def test_switch_in_one_call(oracle, pipelined):
     """kv_switch = plan + block copy + table rewrite + weight stream; byte-identical to the
